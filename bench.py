@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged KV-cache pull on one MI355X.
+
+One "step" is one pass of the whole transfer path for one batch of synthetic requests:
+reset the plan, translate + coalesce every request's block tables (kvd_build_descriptors),
+and move the bytes (kvd_pull).  Pools and their contents are resident in HBM before the
+timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+METRIC = "achieved HBM GB/s (% of peak) for paged KV pull; µs per 8K-token request"
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg_no: int, budget_s: float = 12.0) -> dict:
+    """Time the oracle (as it stands, one thread) on a bounded sample: layer 0 of the same
+    workload, repeated until about `budget_s` seconds of CPU work have been spent."""
+    import numpy as np
+    import kvd_testlib as tl
+    from paper_2501_14743_amd import workloads as wl
+
+    full = wl.CONFIGS[cfg_no]()
+    gs = wl.PoolGeometry(1, full.src.num_blocks, full.src.block_tokens, full.src.num_kv_heads,
+                         full.src.head_dim, full.src.elem_bytes, full.src.layout)
+    gd = wl.PoolGeometry(1, full.dst.num_blocks, full.dst.block_tokens, full.dst.num_kv_heads,
+                         full.dst.head_dim, full.dst.elem_bytes, full.dst.layout)
+    w = wl.Workload(full.name, gs, gd, full.requests, full.dtype, full.seed)
+    src = np.ones(gs.total_bytes, np.uint8)
+    dst = np.ones(gd.total_bytes, np.uint8)
+    payload = w.total_tokens * 2 * gs.num_kv_heads * gs.head_dim * gs.elem_bytes
+    t0 = time.perf_counter()
+    tl.oracle_pull_workload(w, src, dst)
+    first = time.perf_counter() - t0
+    reps = max(1, min(32, int(budget_s / max(first, 1e-3))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        tl.oracle_pull_workload(w, src, dst)
+    dt = (time.perf_counter() - t0) / reps
+    return {
+        "value": 2 * payload / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"layer 0 (K and V) of {full.name}: {w.total_tokens} tokens, {payload} payload bytes, "
+                  f"mean of {reps} passes after one untimed pass; host has {os.cpu_count()} cpus",
+        "seconds_per_layer": dt,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the reported GPU baselines")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch the plain copy kernel a few times (for counter calibration runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (both pools live in one MI355X's HBM); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2501_14743_amd import kvd, workloads as wl
+    import kvd_gpu as G
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    kvd.lib()  # fail now if the library is missing
+    torch.cuda.set_device(0)
+    w = wl.CONFIGS[args.config]()
+    log(f"{w.name}: pools {w.src.total_bytes / 2**30:.2f} + {w.dst.total_bytes / 2**30:.2f} GiB, "
+        f"{len(w.requests)} requests, {w.total_tokens} tokens")
+    src = G.device_random_pool(w.src, w.dtype, w.seed)
+    dst = G.device_sentinel_pool(w.dst)
+    stream = torch.cuda.Stream()
+    x = G.GpuTransfer(w, src, dst, stream=stream)
+    sh = stream.cuda_stream
+
+    def step(ev=None):
+        x.plan.reset()
+        x.build()
+        if ev is not None:
+            ev[0].record(stream)
+        x.plan.pull(sh)
+        if ev is not None:
+            ev[1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stats = x.plan.stats(sh)
+    payload = stats["payload_bytes"]
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pull_ms = np.array([a.elapsed_time(b) for a, b in events])
+    ms_per_step = elapsed / args.steps * 1e3
+    value = 2 * payload * args.steps / elapsed / 1e9
+    achieved = 2 * payload / (pull_ms.mean() * 1e-3) / 1e9
+    log(f"step {ms_per_step * 1e3:.1f} us, pull kernel mean {pull_ms.mean() * 1e3:.1f} us "
+        f"(min {pull_ms.min() * 1e3:.1f}), {achieved:.0f} GB/s = {achieved / PEAK_HBM_GBPS:.1%} of peak")
+
+    # the timed work produced the right bytes: oracle on one layer
+    check_layer = w.layer_end - 1
+    G.compare_layer_with_oracle(w, src, dst, check_layer)
+    log(f"layer {check_layer} matches the oracle")
+
+    extras = {}
+    if not args.no_extras:
+        def timed(fn, reps):
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps * 1e3  # us
+
+        # build alone (host validation + one translate/coalesce kernel per request)
+        def build_only():
+            x.plan.reset()
+            x.build()
+        t = time.perf_counter()
+        for _ in range(20):
+            build_only()
+        torch.cuda.synchronize()
+        extras["build_us"] = (time.perf_counter() - t) / 20 * 1e6
+        # practical ceilings: one contiguous device-to-device copy of the payload
+        n = min(payload, 1 << 30)
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        with torch.cuda.stream(stream):
+            us = timed(lambda: b.copy_(a, non_blocking=True), 10)
+            extras["contiguous_memcpy_GBps"] = 2 * n / us / 1e3
+            us = timed(lambda: kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr(), n, sh), 10)
+            extras["plain_copy_kernel_GBps"] = 2 * n / us / 1e3
+        del a, b
+        # the same plan without coalescing (every block its own descriptor)
+        y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_NO_COALESCE, stream=stream)
+        y.build()
+        us = timed(lambda: y.plan.pull(sh), 10)
+        extras["no_coalesce_pull_us"] = us
+        extras["no_coalesce_descriptors"] = y.plan.stats(sh)["num_descriptors"]
+        y.close()
+        # one hipMemcpyAsync per (layer, K/V, block)
+        if not stats["relayout"]:
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            x.plan.pull_blockwise_memcpy(sh)
+            torch.cuda.synchronize()
+            extras["blockwise_memcpy_us"] = (time.perf_counter() - t) * 1e6
+        log(f"extras: {extras}")
+
+    if args.copy_calibration:
+        n = 1 << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr(), n, sh)
+        torch.cuda.synchronize()
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": w.name, "requests": len(w.requests), "tokens": w.total_tokens,
+                   "layers": w.layer_end - w.layer_begin, "kv_heads": w.src.num_kv_heads,
+                   "head_dim": w.src.head_dim, "elem_bytes": w.src.elem_bytes,
+                   "block_tokens": [w.src.block_tokens, w.dst.block_tokens],
+                   "layouts": [w.src.layout, w.dst.layout], "pool_blocks": [w.src.num_blocks, w.dst.num_blocks],
+                   "payload_bytes": payload, "descriptors": stats["num_descriptors"],
+                   "transactions": stats["num_transactions"]},
+        "us_per_request_batch": ms_per_step * 1e3,
+        "pct_of_peak": 100.0 * achieved / PEAK_HBM_GBPS,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBPS, "traffic": None,
+                     "kernel": "kvd_pull_kernel", "kernel_us_mean": float(pull_ms.mean() * 1e3),
+                     "kernel_us_min": float(pull_ms.min() * 1e3),
+                     "algorithmic_bytes_per_launch": 2 * payload},
+        "verified": f"layer {check_layer} bit-exact vs oracle after the timed steps",
+        "extras": extras,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the oracle on the host")
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out), flush=True)
+    x.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,219 @@
+/*
+ * kvd - paged KV-cache pull for MI355X (gfx950).
+ *
+ * C ABI of the KV-cache transfer path of KVDirect (arXiv 2501.14743): one request's KV cache,
+ * for every layer and for both K and V, is moved out of a source ("remote", prefill) paged
+ * block pool addressed through its block table into a destination ("local", decode) paged
+ * pool under a different block table.  The destination side initiates the copy (pull mode,
+ * section 4.3) and the copies are described by block ids plus tensor metadata (section 4.1),
+ * not by per-block messages.
+ *
+ * The three operations of section 4.1 map onto this interface as follows:
+ *   Connect()   -> kvd_pool_create (x2) + kvd_plan_create : the tensor metadata of both sides
+ *                  is registered once; the memory stays owned by the caller.
+ *   Transfer()  -> kvd_build_descriptors : block ids are translated to byte ranges and queued;
+ *                  queued ranges are coalesced (section 4.2);
+ *                  kvd_pull : every (merged or unmerged) range is issued at once, no waiting
+ *                  in between.
+ *   Complete()  -> the caller's stream order / event after kvd_pull.
+ *
+ * Conventions
+ *   - Every call returns KVD_OK (0) or a negative kvd_status_t; kvd_last_error() gives a
+ *     thread-local message for the last failure on the calling thread.  Nothing aborts or
+ *     throws across this boundary.
+ *   - Pointers are HOST pointers unless the comment says DEVICE.
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the null stream).
+ *     Work is enqueued asynchronously; results are visible after the stream is synchronised.
+ *   - Handles are not thread-safe: use one plan from one thread at a time.
+ *   - The library never allocates, frees or writes the pools' memory except for the bytes a
+ *     pull is defined to write.
+ */
+#ifndef KVD_H
+#define KVD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVD_OK = 0,
+    KVD_ERR_INVALID = -1,  /* null pointer, zero dimension, empty layer range, misalignment       */
+    KVD_ERR_RANGE = -2,    /* block id outside the pool, layer range outside a pool, table short  */
+    KVD_ERR_MISMATCH = -3, /* the two pools do not hold the same kind of element / unsupported pair */
+    KVD_ERR_ALIAS = -4,    /* a destination block is used twice in one plan, or the pools overlap  */
+    KVD_ERR_CAPACITY = -5, /* plan is full                                                         */
+    KVD_ERR_HIP = -6       /* a HIP runtime call failed (message holds the HIP error)              */
+} kvd_status_t;
+
+/* Order of the axes inside one block of one of K / V (section 4.1: the order of the
+ * dimensions is free and part of the metadata). */
+typedef enum {
+    KVD_LAYOUT_BHTD = 0, /* [block][head][token][dim] */
+    KVD_LAYOUT_BTHD = 1  /* [block][token][head][dim] */
+} kvd_layout_t;
+
+/*
+ * Tensor metadata of one pool: Address, Shape and Stride of section 4.1, for all layers at
+ * once.  Element (layer, kv, block, token, head, dim) lives at element offset
+ *   layer*stride_layer + kv*stride_kv + block*stride_block + inner(token, head)*head_dim + dim
+ * with inner = head*block_tokens + token (BHTD) or token*num_kv_heads + head (BTHD); the
+ * axes inside a block are dense.  Strides count elements.
+ * Requirements (else KVD_ERR_INVALID): base, stride_*xelem_bytes and head_dim*elem_bytes are
+ * multiples of 16 bytes; elem_bytes is 1, 2, 4 or 8; stride_block >= elements of one block;
+ * block_tokens <= 1024.  The block axis of one (layer, kv) slab may span at most 64 GiB
+ * (KVD_ERR_RANGE).
+ */
+typedef struct {
+    void *base; /* DEVICE pointer, borrowed for the pool's lifetime */
+    uint32_t num_layers;
+    uint32_t num_blocks;
+    uint32_t block_tokens;
+    uint32_t num_kv_heads;
+    uint32_t head_dim;
+    uint32_t elem_bytes;
+    int32_t layout; /* kvd_layout_t */
+    int64_t stride_layer;
+    int64_t stride_kv;
+    int64_t stride_block;
+} kvd_pool_desc_t;
+
+typedef struct kvd_pool kvd_pool_t;
+typedef struct kvd_plan kvd_plan_t;
+
+/* kvd_plan_create flags */
+#define KVD_PLAN_NO_COALESCE 1u /* keep every read transaction separate (ablation of section 4.2) */
+
+/* A coalesced read transaction of the byte-copy path, relative to (layer 0, K): the copy for
+ * (layer, kv) adds layer*stride_layer*elem_bytes + kv*stride_kv*elem_bytes of the respective
+ * pool to both offsets. */
+typedef struct {
+    uint64_t src_offset; /* bytes from the source pool's base       */
+    uint64_t dst_offset; /* bytes from the destination pool's base  */
+    uint64_t bytes;
+} kvd_span_t;
+
+/* A read transaction of the re-layout path: num_tokens tokens that sit in one source block
+ * and one destination block. */
+typedef struct {
+    int32_t src_block;
+    uint32_t src_token; /* first slot inside the source block      */
+    int32_t dst_block;
+    uint32_t dst_token; /* first slot inside the destination block */
+    uint32_t num_tokens;
+} kvd_piece_t;
+
+typedef struct {
+    uint32_t num_requests;
+    uint32_t num_segments;     /* descriptor groups staged one after another by the pull kernel */
+    uint32_t relayout;         /* 0: byte-copy path, 1: re-layout path                           */
+    uint32_t reserved;
+    uint64_t num_src_blocks;   /* table entries consumed on the source side                      */
+    uint64_t num_dst_blocks;   /* table entries consumed on the destination side                 */
+    uint64_t num_transactions; /* read transactions before coalescing, per (layer, kv)           */
+    uint64_t num_descriptors;  /* after coalescing, per (layer, kv)                              */
+    uint64_t payload_bytes;    /* bytes one kvd_pull writes = bytes it reads                     */
+} kvd_stats_t;
+
+/*
+ * Register one pool's tensor metadata (section 4.1, what Connect() exchanges; the pool's
+ * memory plays the role of the registered GPU memory region of section 4.2).
+ * `desc` is copied.  No GPU call is made.  *out receives a handle to release with kvd_free.
+ * Errors: KVD_ERR_INVALID, KVD_ERR_RANGE (see kvd_pool_desc_t).
+ */
+int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out);
+
+/*
+ * Create a transfer plan from `src` to `dst`: the transaction queue of section 4.2.  A plan
+ * holds the requests appended by kvd_build_descriptors until kvd_plan_reset.
+ * max_requests / max_total_blocks bound the number of appended requests and the number of
+ * block-table entries (per side) the plan can hold.  The pool metadata is copied, so the pool
+ * handles may be freed before the plan.  Device and pinned scratch memory (a few bytes per
+ * block) is allocated by the first kvd_build_descriptors that passes validation, on the
+ * device that is current then.
+ * Errors: KVD_ERR_INVALID (null, zero capacity), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
+ * elem_bytes differ; block sizes of which neither divides the other), KVD_ERR_ALIAS (the byte
+ * ranges of the two pools overlap).
+ */
+int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_requests,
+                    uint32_t max_total_blocks, uint32_t flags, kvd_plan_t **out);
+
+/*
+ * Append one request: Transfer() for each of its blocks (section 4.1), queued behind the
+ * requests already in the plan, then coalesced with them (section 4.2: a transaction is
+ * merged into its predecessor in the queue only when it continues it on both the source and
+ * the destination side; merges may cross request boundaries).
+ *
+ * src_block_table[n_src], dst_block_table[n_dst]: HOST arrays of physical block ids in
+ * logical order; token t of the request is in source block src_block_table[t / Tsrc] slot
+ * t % Tsrc and goes to destination block dst_block_table[t / Tdst] slot t % Tdst.  Only the
+ * first ceil(seq_len / T) entries of each table are used; both arrays may be reused by the
+ * caller as soon as the call returns.  Only tokens below seq_len are moved: the unused slots
+ * of the last destination block keep their contents.  Layers [layer_begin, layer_end) are
+ * moved, K and V.  seq_len == 0 appends nothing and succeeds.
+ *
+ * Address translation and coalescing run in a kernel enqueued on `stream`; kvd_pull must be
+ * enqueued on the same stream (or be ordered after it by the caller).
+ *
+ * Errors (checked on the host before anything is enqueued; the plan is unchanged on error):
+ * KVD_ERR_INVALID (null, layer_begin >= layer_end), KVD_ERR_RANGE (block id outside its pool,
+ * layer range outside either pool, a table shorter than ceil(seq_len / T)), KVD_ERR_ALIAS (a
+ * destination block already used in this plan, or twice in this request; repeated source
+ * blocks are allowed), KVD_ERR_CAPACITY, KVD_ERR_HIP.
+ */
+int kvd_build_descriptors(kvd_plan_t *plan, const int32_t *src_block_table, uint32_t n_src,
+                          const int32_t *dst_block_table, uint32_t n_dst, uint32_t seq_len,
+                          uint32_t layer_begin, uint32_t layer_end, void *stream);
+
+/*
+ * Issue every queued (merged or unmerged) read of the plan at once, for all its requests,
+ * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
+ * blocking; section 4.3: all layers in a single shot).  May be called repeatedly; a plan with
+ * no requests is a no-op.  Completion (section 4.1, Complete()) is the caller's
+ * synchronisation on `stream`.
+ * Errors: KVD_ERR_INVALID, KVD_ERR_HIP.
+ */
+int kvd_pull(kvd_plan_t *plan, void *stream);
+
+/*
+ * Reported baseline, not the product path: the same transfer as one hipMemcpyAsync per
+ * (request, layer, K/V, block) on `stream`, the way a per-block message scheme touches memory
+ * (section 3, motivation 1).  Only for pools with equal layout and block size
+ * (else KVD_ERR_MISMATCH).
+ */
+int kvd_pull_blockwise_memcpy(kvd_plan_t *plan, void *stream);
+
+/* Forget all requests of the plan (waits for the plan's own staging copies, not for pulls:
+ * the caller must not reset while a build or pull of this plan is still running). */
+int kvd_plan_reset(kvd_plan_t *plan);
+
+/* Counters of the plan.  Synchronises `stream` (the one the builds were enqueued on) to read
+ * the descriptor counts back. */
+int kvd_plan_stats(kvd_plan_t *plan, void *stream, kvd_stats_t *out);
+
+/*
+ * Read the plan's descriptors back (synchronises `stream`).  Byte-copy plans fill `spans`
+ * (pieces may be NULL), re-layout plans fill `pieces`.  At most `cap` entries are written;
+ * *n_out receives the number available.  Order is queue order.
+ */
+int kvd_plan_get_descriptors(kvd_plan_t *plan, void *stream, kvd_span_t *spans,
+                             kvd_piece_t *pieces, uint64_t cap, uint64_t *n_out);
+
+/*
+ * Plain streaming copy of `bytes` bytes (multiple of 16, DEVICE pointers 16-byte aligned) with
+ * the same access width as the pull kernel.  Used to calibrate hardware byte counters and as
+ * the practical copy ceiling next to which the pull is reported.
+ */
+int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream);
+
+/* Release a pool or a plan (NULL is allowed).  Frees the plan's own scratch, never pool memory. */
+void kvd_free(void *handle);
+
+/* Message for the last error on this thread ("" if none). */
+const char *kvd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVD_H */

@@ -53,16 +53,23 @@ int64_t kvdo_offset_bytes(const kvdo_tensor *t, const int64_t index[5])
     return dot * t->elem_bytes;
 }
 
-/* Same dot product with the index given by role (block, kv, token, head, dim). */
-static int64_t offset_by_role(const kvdo_tensor *t, int64_t b, int64_t kv,
+/* Same dot product with the index given by role (block, kv, token, head, dim);
+ * role_axis[r] is the axis that plays role r (see roles_to_axes). */
+static void roles_to_axes(const kvdo_tensor *t, int role_axis[5])
+{
+    for (int r = 0; r < 5; ++r)
+        role_axis[r] = axis_of(t, r);
+}
+
+static int64_t offset_by_role(const kvdo_tensor *t, const int role_axis[5], int64_t b, int64_t kv,
                               int64_t l, int64_t h, int64_t d)
 {
     int64_t index[5];
-    index[axis_of(t, KVDO_B)] = b;
-    index[axis_of(t, KVDO_KV)] = kv;
-    index[axis_of(t, KVDO_L)] = l;
-    index[axis_of(t, KVDO_H)] = h;
-    index[axis_of(t, KVDO_D)] = d;
+    index[role_axis[KVDO_B]] = b;
+    index[role_axis[KVDO_KV]] = kv;
+    index[role_axis[KVDO_L]] = l;
+    index[role_axis[KVDO_H]] = h;
+    index[role_axis[KVDO_D]] = d;
     return kvdo_offset_bytes(t, index);
 }
 
@@ -108,6 +115,9 @@ int kvdo_pull(const kvdo_tensor *src, const kvdo_tensor *dst,
     for (int64_t layer = layer_begin; layer < layer_end; ++layer) {
         const kvdo_tensor *s = &src[layer];
         const kvdo_tensor *d = &dst[layer];
+        int sa[5], da[5];
+        roles_to_axes(s, sa);
+        roles_to_axes(d, da);
         const int64_t Ls = s->shape[axis_of(s, KVDO_L)];
         const int64_t Ld = d->shape[axis_of(d, KVDO_L)];
         const int64_t H = s->shape[axis_of(s, KVDO_H)];
@@ -120,8 +130,8 @@ int kvdo_pull(const kvdo_tensor *src, const kvdo_tensor *dst,
             for (int64_t t = 0; t < seq_len; ++t)
                 for (int64_t h = 0; h < H; ++h)
                     for (int64_t x = 0; x < D; ++x) {
-                        int64_t so = offset_by_role(s, src_table[t / Ls], kv, t % Ls, h, x);
-                        int64_t dofs = offset_by_role(d, dst_table[t / Ld], kv, t % Ld, h, x);
+                        int64_t so = offset_by_role(s, sa, src_table[t / Ls], kv, t % Ls, h, x);
+                        int64_t dofs = offset_by_role(d, da, dst_table[t / Ld], kv, t % Ld, h, x);
                         memcpy(d->address + dofs, s->address + so, (size_t)e);
                     }
     }
@@ -163,6 +173,9 @@ int64_t kvdo_request_transactions(const kvdo_tensor *s, const kvdo_tensor *d, in
     const int64_t D = s->shape[axis_of(s, KVDO_D)];
     const int64_t e = s->elem_bytes;
     const int64_t max_tokens = Ls < Ld ? Ls : Ld;
+    int sa[5], da[5];
+    roles_to_axes(s, sa);
+    roles_to_axes(d, da);
     kvdo_txn *elems = (kvdo_txn *)malloc((size_t)(max_tokens * H * D) * sizeof(kvdo_txn));
     int64_t n_out = 0;
     int64_t t0 = 0;
@@ -175,8 +188,8 @@ int64_t kvdo_request_transactions(const kvdo_tensor *s, const kvdo_tensor *d, in
         for (int64_t t = t0; t < t1; ++t)
             for (int64_t h = 0; h < H; ++h)
                 for (int64_t x = 0; x < D; ++x) {
-                    elems[n].remote = offset_by_role(s, src_table[t / Ls], kv, t % Ls, h, x);
-                    elems[n].local = offset_by_role(d, dst_table[t / Ld], kv, t % Ld, h, x);
+                    elems[n].remote = offset_by_role(s, sa, src_table[t / Ls], kv, t % Ls, h, x);
+                    elems[n].local = offset_by_role(d, da, dst_table[t / Ld], kv, t % Ld, h, x);
                     elems[n].size = e;
                     ++n;
                 }

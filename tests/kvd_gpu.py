@@ -1,0 +1,107 @@
+"""GPU-side test plumbing: device pools as torch byte tensors, running a workload through the
+C ABI, and slab-wise comparison with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import kvd_testlib as tl
+from paper_2501_14743_amd import kvd
+from paper_2501_14743_amd import workloads as wl
+
+DEV = "cuda:0"
+
+
+def device_pool_from_host(host_bytes: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(host_bytes).to(DEV)
+
+
+def device_sentinel_pool(g: wl.PoolGeometry) -> torch.Tensor:
+    t = torch.empty(g.total_bytes, dtype=torch.uint8, device=DEV)
+    t.view(torch.int16).fill_(wl.SENTINEL16)
+    return t
+
+
+def device_random_pool(g: wl.PoolGeometry, dtype: str, seed: int) -> torch.Tensor:
+    """N(0,1) in fp16 / bf16 everywhere, generated on the device layer by layer."""
+    assert g.elem_bytes == 2
+    t = torch.empty(g.total_bytes, dtype=torch.uint8, device=DEV)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    td = torch.float16 if dtype == "fp16" else torch.bfloat16
+    v = t.view(td).view(g.num_layers, g.stride_layer)
+    for layer in range(g.num_layers):
+        v[layer].normal_(generator=gen)
+    return t
+
+
+class GpuTransfer:
+    """Pools + plan for one workload on the GPU."""
+
+    def __init__(self, w: wl.Workload, src: torch.Tensor, dst: torch.Tensor, flags: int = 0,
+                 stream: torch.cuda.Stream | None = None):
+        self.w, self.src, self.dst = w, src, dst
+        self.stream = stream or torch.cuda.Stream(device=DEV)
+        self.src_pool = kvd.Pool(src.data_ptr(), w.src)
+        self.dst_pool = kvd.Pool(dst.data_ptr(), w.dst)
+        max_blocks = sum(max(len(r.src_table), len(r.dst_table)) for r in w.requests) + 1
+        self.plan = kvd.Plan(self.src_pool, self.dst_pool, max(1, len(w.requests)), max_blocks, flags)
+
+    def build(self):
+        for r in self.w.requests:
+            self.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, self.w.layer_begin,
+                                        self.w.layer_end, self.stream.cuda_stream)
+
+    def pull(self):
+        self.plan.pull(self.stream.cuda_stream)
+
+    def run(self):
+        self.build()
+        self.pull()
+        self.stream.synchronize()
+        return self
+
+    def close(self):
+        self.plan.close()
+        self.src_pool.close()
+        self.dst_pool.close()
+
+
+def oracle_expected(w: wl.Workload, src_host: np.ndarray) -> np.ndarray:
+    dst = wl.host_pool_sentinel(w.dst)
+    tl.oracle_pull_workload(w, src_host, dst)
+    return dst
+
+
+def assert_bytes_equal(got: np.ndarray, want: np.ndarray, what: str = ""):
+    if not np.array_equal(got, want):
+        bad = np.nonzero(got != want)[0]
+        raise AssertionError(f"{what}: {bad.size} bytes differ, first at byte {int(bad[0])} "
+                             f"(got {int(got[bad[0]])}, want {int(want[bad[0]])})")
+
+
+def run_and_compare(w: wl.Workload, src_host: np.ndarray, flags: int = 0):
+    """Whole-pool, element-by-element comparison of the GPU result with the oracle."""
+    src = device_pool_from_host(src_host)
+    dst = device_sentinel_pool(w.dst)
+    x = GpuTransfer(w, src, dst, flags).run()
+    want = oracle_expected(w, src_host)
+    assert_bytes_equal(dst.cpu().numpy(), want, w.name)
+    assert_bytes_equal(src.cpu().numpy(), src_host, w.name + " (source changed)")
+    return x
+
+
+def compare_layer_with_oracle(w: wl.Workload, src: torch.Tensor, dst: torch.Tensor, layer: int):
+    """Oracle for one layer of a large workload: copies that layer's slabs to the host."""
+    gs, gd = w.src, w.dst
+    sb, db = gs.stride_layer * gs.elem_bytes, gd.stride_layer * gd.elem_bytes
+    src_host = src[layer * sb:(layer + 1) * sb].cpu().numpy()
+    got = dst[layer * db:(layer + 1) * db].cpu().numpy()
+    want = np.full(db // 2, wl.SENTINEL16, dtype=np.uint16).view(np.uint8)
+    if w.layer_begin <= layer < w.layer_end:
+        s = tl.oracle_tensors(gs, src_host, first_layer=layer, num_layers=1)
+        d = tl.oracle_tensors(gd, want, first_layer=layer, num_layers=1)
+        from oracle import kvd_oracle as orc
+        for r in w.requests:
+            orc.pull(s, d, layer, layer + 1, r.src_table, r.dst_table, r.seq_len)
+    assert_bytes_equal(got, want, f"{w.name} layer {layer}")

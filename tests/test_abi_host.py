@@ -1,0 +1,134 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2501_14743_amd import kvd
+from paper_2501_14743_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_SRC = 0x10_0000_0000  # never dereferenced: no kernel is launched in this file
+FAKE_DST = 0x20_0000_0000
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "kvd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert {"kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_pull", "kvd_free",
+            "kvd_last_error"} <= set(names)
+    L = kvd.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_binding_mirrors_every_declared_symbol():
+    for n in header_functions():
+        assert callable(getattr(kvd, n)), n
+
+
+def geom(**kw):
+    base = dict(num_layers=2, num_blocks=64, block_tokens=16, num_kv_heads=4, head_dim=64, elem_bytes=2,
+                layout=wl.BHTD)
+    base.update(kw)
+    return wl.PoolGeometry(**base)
+
+
+def expect(code, fn, *a, **k):
+    with pytest.raises(kvd.KvdError) as e:
+        fn(*a, **k)
+    assert e.value.code == code, str(e.value)
+    assert kvd.kvd_last_error() != ""
+    return str(e.value)
+
+
+def test_pool_create_rejects_bad_metadata():
+    g = geom()
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, 0, g)                       # null base
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC + 8, g)            # misaligned base
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(head_dim=4))  # 8-byte rows
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(num_kv_heads=0))
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(elem_bytes=3))
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, g, stride_block=g.tile_elems - 8)
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(block_tokens=2048))
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pool_create, FAKE_SRC, 2, 64, 16, 4, 64, 2, 7, 1 << 20, 1 << 19, 4096)
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8))
+    p = kvd.Pool(FAKE_SRC, g)
+    assert p.handle
+    p.close()
+    kvd.kvd_free(None)
+
+
+def test_plan_create_rejects_mismatch_and_overlap():
+    g = geom()
+    s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(num_kv_heads=2)), 1, 8)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(head_dim=128)), 1, 8)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(elem_bytes=4)), 1, 8)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(block_tokens=24)), 1, 8)
+    expect(kvd.KVD_ERR_ALIAS, kvd.Plan, s, s, 1, 8)
+    expect(kvd.KVD_ERR_ALIAS, kvd.Plan, s, kvd.Pool(FAKE_SRC + g.total_bytes - 4096, g), 1, 8)
+    expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 0, 8)
+    expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 1, 0)
+    # touching but not overlapping is fine
+    kvd.Plan(s, kvd.Pool(FAKE_SRC + g.total_bytes, g), 1, 8).close()
+    with pytest.raises(kvd.KvdError):
+        kvd.kvd_plan_create(s.handle, 0, 1, 8)
+
+
+def test_build_descriptors_validates_before_launching():
+    g = geom()
+    s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
+    plan = kvd.Plan(s, d, 2, 8)
+    ok = np.arange(8, dtype=np.int32)
+    expect(kvd.KVD_ERR_INVALID, plan.build_descriptors, ok, ok, 128, 1, 1)        # empty layer range
+    expect(kvd.KVD_ERR_INVALID, plan.build_descriptors, ok, ok, 128, 2, 1)
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, ok, ok, 128, 0, 3)          # layers outside pool
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, ok[:7], ok, 128, 0, 2)      # source table short
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, ok, ok[:7], 113, 0, 2)      # destination table short
+    bad = ok.copy(); bad[3] = 64
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, bad, ok, 128, 0, 2)
+    bad[3] = -1
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, ok, bad, 128, 0, 2)
+    dup = ok.copy(); dup[5] = dup[2]
+    msg = expect(kvd.KVD_ERR_ALIAS, plan.build_descriptors, ok, dup, 128, 0, 2)   # destination block twice
+    assert "destination block 2" in msg
+    expect(kvd.KVD_ERR_CAPACITY, plan.build_descriptors, np.arange(9), np.arange(9), 144, 0, 2)
+    # entries beyond ceil(seq_len / block_tokens) are ignored, even invalid ones
+    long_tbl = np.array([0, 1, 99999], dtype=np.int32)
+    # seq_len 0 appends nothing and succeeds, whatever the tables hold
+    plan.build_descriptors(long_tbl, long_tbl, 0, 0, 2)
+    assert plan.stats()["num_requests"] == 0
+    # a pull of an empty plan is a no-op
+    plan.pull()
+    plan.reset()
+    with pytest.raises(kvd.KvdError):
+        kvd.kvd_pull(0)
+
+
+def test_valid_build_needs_a_gpu_and_says_so():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present: covered by the gpu tests")
+    g = geom()
+    plan = kvd.Plan(kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g), 2, 8)
+    ok = np.arange(8, dtype=np.int32)
+    msg = expect(kvd.KVD_ERR_HIP, plan.build_descriptors, ok, ok, 128, 0, 2)
+    assert "hip" in msg.lower()
+    # the failed call left no trace: the same destination blocks can be used again
+    expect(kvd.KVD_ERR_HIP, plan.build_descriptors, ok, ok, 128, 0, 2)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(kvd, "_lib", None)
+    monkeypatch.setattr(kvd, "LIB_PATH", "/nonexistent/libkvd.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        kvd.kvd_pull(1)

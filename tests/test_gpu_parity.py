@@ -1,0 +1,337 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, bit for bit.
+
+Small cases compare whole pools element by element; the full-size configurations compare
+sampled layers with the oracle and check size-independent properties on every layer."""
+import numpy as np
+import pytest
+import torch
+
+import kvd_testlib as tl
+from paper_2501_14743_amd import kvd
+from paper_2501_14743_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import kvd_gpu as G
+
+
+def say(msg):
+    print(f"[kvd-test] {msg}", flush=True)
+
+
+def host_src(w, seed=None):
+    return wl.host_pool_values(w.src, w.dtype, w.seed if seed is None else seed)
+
+
+# ------------------------------------------------------------------ the five configurations, reduced
+
+def reduced_configs():
+    return [
+        wl.config1(),
+        wl.config2(num_layers=2, pool_blocks=2048, tokens=8192),
+        wl.config3(num_layers=2, num_requests=16, median=256.0, hi=2048),
+        wl.config4(num_layers=4, pool_blocks=2048, tokens=8192),
+        wl.config5(num_layers=2, src_pool_blocks=512, tokens=2000),
+    ]
+
+
+@pytest.mark.parametrize("w", reduced_configs(), ids=lambda w: w.name)
+def test_reduced_configs_match_oracle(w):
+    say(f"{w.name}: {len(w.requests)} requests, {w.total_tokens} tokens")
+    x = G.run_and_compare(w, host_src(w))
+    st = x.plan.stats(x.stream.cuda_stream)
+    assert st["num_requests"] == len(w.requests)
+    assert st["payload_bytes"] == w.total_tokens * (w.layer_end - w.layer_begin) * 2 * \
+        w.src.num_kv_heads * w.src.head_dim * w.src.elem_bytes
+    x.close()
+
+
+@pytest.mark.parametrize("w", reduced_configs()[:4], ids=lambda w: w.name)
+def test_descriptors_equal_oracle_coalescing(w):
+    """Byte-copy plans: the compacted descriptor list is exactly the oracle's merged queue."""
+    src = G.device_sentinel_pool(w.src)
+    dst = G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, dst)
+    x.build()
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    st = x.plan.stats(x.stream.cuda_stream)
+    assert st["num_segments"] == 1 and st["relayout"] == 0
+    want = tl.oracle_plan_descriptors(w, 0, 0)
+    assert np.array_equal(got, want)
+    assert st["num_descriptors"] == len(want) <= st["num_transactions"]
+    # and for another (layer, K/V) tensor the same list shifted by the slab strides
+    want_v = tl.oracle_plan_descriptors(w, 1, 1)
+    shift_s = (w.src.stride_layer + w.src.stride_kv) * w.src.elem_bytes
+    shift_d = (w.dst.stride_layer + w.dst.stride_kv) * w.dst.elem_bytes
+    assert np.array_equal(got + np.array([shift_s, shift_d, 0]), want_v)
+    x.close()
+
+
+def test_no_coalesce_flag_keeps_every_transaction_and_same_bytes():
+    w = wl.config2(num_layers=2, pool_blocks=1024, tokens=3000)
+    x = G.run_and_compare(w, host_src(w), flags=kvd.KVD_PLAN_NO_COALESCE)
+    st = x.plan.stats(x.stream.cuda_stream)
+    assert st["num_descriptors"] == st["num_transactions"] == 187 + 8  # 187 whole blocks + 8 head rows
+    x.close()
+
+
+def test_relayout_pieces():
+    w = wl.config5(num_layers=1, src_pool_blocks=64, tokens=100)
+    x = G.GpuTransfer(w, G.device_sentinel_pool(w.src), G.device_sentinel_pool(w.dst))
+    x.build()
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    r = w.requests[0]
+    want = [(r.src_table[p], 0, r.dst_table[p // 2], (p % 2) * 16, min(16, 100 - 16 * p)) for p in range(7)]
+    assert got.tolist() == [list(map(int, t)) for t in want]
+    x.close()
+
+
+# ------------------------------------------------------------------ edge cases
+
+def small_geom(**kw):
+    base = dict(num_layers=3, num_blocks=96, block_tokens=16, num_kv_heads=4, head_dim=64, elem_bytes=2,
+                layout=wl.BHTD)
+    base.update(kw)
+    return wl.PoolGeometry(**base)
+
+
+def one_request(gs, gd, tokens, seed=5, **kw):
+    rng = np.random.default_rng(seed)
+    return wl.Workload(f"edge-{tokens}", gs, gd, [wl.Request(
+        tokens, wl.permutation_table(rng, gs.num_blocks, wl.blocks_for(tokens, gs.block_tokens)),
+        wl.permutation_table(rng, gd.num_blocks, wl.blocks_for(tokens, gd.block_tokens)))], "bf16", seed, **kw)
+
+
+@pytest.mark.parametrize("tokens", [1, 15, 16, 17, 255, 1000])
+@pytest.mark.parametrize("layout", [wl.BHTD, wl.BTHD])
+def test_ragged_lengths(tokens, layout):
+    g = small_geom(layout=layout)
+    w = one_request(g, g, tokens)
+    say(f"ragged {layout} {tokens}")
+    G.run_and_compare(w, host_src(w)).close()
+
+
+@pytest.mark.parametrize("gs,gd", [
+    (small_geom(block_tokens=8, num_blocks=192), small_geom(block_tokens=16)),                       # head-major, 8 -> 16
+    (small_geom(block_tokens=32, num_blocks=48), small_geom(block_tokens=8, num_blocks=192)),                       # head-major, 32 -> 8
+    (small_geom(layout=wl.BTHD), small_geom(layout=wl.BTHD, block_tokens=32, num_blocks=48)),       # token-major 16 -> 32
+    (small_geom(), small_geom(layout=wl.BTHD)),                                                     # re-layout, equal block size
+    (small_geom(layout=wl.BTHD, block_tokens=32, num_blocks=48), small_geom()),                     # re-layout back, 32 -> 16
+    (small_geom(num_kv_heads=3, head_dim=96), small_geom(num_kv_heads=3, head_dim=96, layout=wl.BTHD, block_tokens=64, num_blocks=24)),
+    (small_geom(num_kv_heads=3, head_dim=96, layout=wl.BTHD), small_geom(num_kv_heads=3, head_dim=96, block_tokens=4, num_blocks=384)),
+    (small_geom(num_kv_heads=1), small_geom(num_kv_heads=1, layout=wl.BTHD, block_tokens=32, num_blocks=48)),  # one head: layouts coincide
+], ids=["hm8-16", "hm32-8", "tm16-32", "relayout-eq", "relayout-back", "relayout-odd", "relayout-odd-back", "one-head"])
+@pytest.mark.parametrize("tokens", [333, 1024])
+def test_mixed_block_sizes_and_layouts(gs, gd, tokens):
+    w = one_request(gs, gd, tokens)
+    say(f"mixed {gs.layout}{gs.block_tokens}->{gd.layout}{gd.block_tokens} {tokens}")
+    G.run_and_compare(w, host_src(w)).close()
+
+
+@pytest.mark.parametrize("elem_bytes,head_dim", [(1, 128), (4, 32), (8, 16)])
+def test_element_sizes(elem_bytes, head_dim):
+    g = small_geom(elem_bytes=elem_bytes, head_dim=head_dim)
+    w = one_request(g, g, 200)
+    rng = np.random.default_rng(1)
+    src = rng.integers(0, 255, size=g.total_bytes, dtype=np.uint8)
+    G.run_and_compare(w, src).close()
+
+
+def test_layer_sub_range_and_mixed_ranges_in_one_plan():
+    g = small_geom(num_layers=4)
+    rng = np.random.default_rng(2)
+    perm_s, perm_d = rng.permutation(96).astype(np.int32), rng.permutation(96).astype(np.int32)
+    src_host = wl.host_pool_values(g, "bf16", 3)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    sp, dp = kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g)
+    plan = kvd.Plan(sp, dp, 4, 96)
+    s = torch.cuda.Stream()
+    reqs = [(100, 0, 10, 1, 3), (50, 10, 14, 1, 3), (77, 14, 19, 0, 4), (16, 19, 20, 3, 4)]
+    want = wl.host_pool_sentinel(g)
+    for tokens, a, b, l0, l1 in reqs:
+        plan.build_descriptors(perm_s[a:b], perm_d[a:b], tokens, l0, l1, s.cuda_stream)
+        w = wl.Workload("r", g, g, [wl.Request(tokens, perm_s[a:b], perm_d[a:b])], "bf16", 0, l0, l1)
+        tl.oracle_pull_workload(w, src_host, want)
+    assert plan.stats(s.cuda_stream)["num_segments"] == 3  # a new group whenever the layer range changes
+    plan.pull(s.cuda_stream)
+    s.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "mixed layer ranges")
+    plan.close()
+
+
+def test_merge_across_requests_as_in_queue_example():
+    # R1 reads block 0 into 5, R2 reads 1 into 6 (+ 3 into 9): first two merge (section 4.2)
+    g = small_geom(num_layers=1)
+    src_host = wl.host_pool_values(g, "bf16", 4)
+    w = wl.Workload("queue", g, g, [wl.Request(16, np.array([0], np.int32), np.array([5], np.int32)),
+                                    wl.Request(32, np.array([1, 3], np.int32), np.array([6, 9], np.int32))],
+                    "bf16", 4)
+    x = G.run_and_compare(w, src_host)
+    d = x.plan.descriptors(x.stream.cuda_stream)
+    tile = g.tile_elems * 2
+    assert d.tolist() == [[0, 5 * tile, 2 * tile], [3 * tile, 9 * tile, tile]]
+    assert np.array_equal(d, tl.oracle_plan_descriptors(w, 0, 0))
+    x.close()
+
+
+def test_many_transactions_span_several_descriptor_groups():
+    # 16-byte rows, one head: 10000 lone blocks -> more transactions than one LDS group holds
+    g = wl.PoolGeometry(2, 20000, 16, 1, 8, 2, wl.BHTD)
+    rng = np.random.default_rng(6)
+    st = wl.scattered_table(rng, g.num_blocks, 10000)
+    dt = wl.scattered_table(rng, g.num_blocks, 10000)
+    w = wl.Workload("groups", g, g, [wl.Request(10000 * 16 - 3, st, dt)], "bf16", 6)
+    x = G.run_and_compare(w, host_src(w))
+    st_ = x.plan.stats(x.stream.cuda_stream)
+    assert st_["num_segments"] == 3 and st_["num_descriptors"] == 10000
+    x.close()
+    # the same with long contiguous runs: merging stops only at group boundaries
+    ident = np.arange(10000, dtype=np.int32)
+    w2 = wl.Workload("groups-contig", g, g, [wl.Request(10000 * 16, ident, ident + 5000)], "bf16", 6)
+    x = G.run_and_compare(w2, host_src(w2))
+    assert x.plan.stats(x.stream.cuda_stream)["num_descriptors"] == 3
+    x.close()
+
+
+def test_padded_block_stride_and_block_major_pool():
+    # blocks padded to 1.5 tiles, K and V of a block next to each other, layers outermost
+    g = small_geom(num_layers=2, num_blocks=32)
+    tile = g.tile_elems
+    stride_block, stride_kv = 3 * tile, tile + tile // 2
+    stride_layer = g.num_blocks * stride_block
+    total = 2 * stride_layer * 2
+    rng = np.random.default_rng(8)
+    src_host = wl.normal_bits(rng, total // 2, "bf16").view(np.uint8)
+    want = np.full(total // 2, wl.SENTINEL16, np.uint16).view(np.uint8)
+    st, dt = rng.permutation(32)[:7].astype(np.int32), rng.permutation(32)[:7].astype(np.int32)
+    from oracle import kvd_oracle as orc
+
+    def tensors(buf):
+        return [orc.Tensor(buf, layer * stride_layer * 2, [orc.KV, orc.B, orc.H, orc.L, orc.D],
+                           [2, 32, 4, 16, 64], [stride_kv, stride_block, 16 * 64, 64, 1], 2) for layer in range(2)]
+    orc.pull(tensors(src_host), tensors(want), 0, 2, st, dt, 100)
+    src, dst = G.device_pool_from_host(src_host), G.device_pool_from_host(want.copy())
+    dst.view(torch.int16).fill_(wl.SENTINEL16)
+    sp = kvd.Pool(src.data_ptr(), g, stride_layer, stride_kv, stride_block)
+    dp = kvd.Pool(dst.data_ptr(), g, stride_layer, stride_kv, stride_block)
+    plan = kvd.Plan(sp, dp, 1, 8)
+    plan.build_descriptors(st, dt, 100, 0, 2)
+    plan.pull()
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "padded strides")
+    plan.close()
+
+
+def test_plan_reuse_reset_repeat_and_round_trip():
+    w = wl.config5(num_layers=2, src_pool_blocks=128, tokens=777)
+    src_host = host_src(w)
+    src, mid = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, mid).run()
+    want = G.oracle_expected(w, src_host)
+    G.assert_bytes_equal(mid.cpu().numpy(), want, "first pull")
+    x.pull(); x.pull()                      # a pull is idempotent
+    x.stream.synchronize()
+    G.assert_bytes_equal(mid.cpu().numpy(), want, "repeated pull")
+    # reset and reuse the plan for another request with other tables
+    x.plan.reset()
+    assert x.plan.stats(x.stream.cuda_stream)["num_requests"] == 0
+    mid.view(torch.int16).fill_(wl.SENTINEL16)
+    r = w.requests[0]
+    w2 = wl.Workload("again", w.src, w.dst, [wl.Request(300, r.src_table[::-1].copy(), r.dst_table[::-1].copy())], "bf16", 0)
+    x.w = w2
+    x.run()
+    G.assert_bytes_equal(mid.cpu().numpy(), G.oracle_expected(w2, src_host), "after reset")
+    x.close()
+    # round trip: pull back through the inverse mapping restores the valid tokens of the source
+    back = G.device_sentinel_pool(w.src)
+    wb = wl.Workload("back", w.dst, w.src, [wl.Request(300, w2.requests[0].dst_table, w2.requests[0].src_table)], "bf16", 0)
+    y = G.GpuTransfer(wb, mid, back).run()
+    b = back.cpu().numpy().view(np.uint16)
+    touched = b != wl.SENTINEL16
+    assert np.count_nonzero(touched) == 300 * 2 * 2 * 8 * 128
+    assert np.array_equal(b[touched], src_host.view(np.uint16)[touched])
+    y.close()
+
+
+def test_blockwise_memcpy_baseline_gives_the_same_bytes():
+    w = wl.config2(num_layers=2, pool_blocks=512, tokens=1000)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, dst)
+    x.build()
+    x.plan.pull_blockwise_memcpy(x.stream.cuda_stream)
+    x.stream.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "blockwise memcpy")
+    x.close()
+    w5 = wl.config5(num_layers=1, src_pool_blocks=64, tokens=64)
+    y = G.GpuTransfer(w5, G.device_sentinel_pool(w5.src), G.device_sentinel_pool(w5.dst))
+    y.build()
+    with pytest.raises(kvd.KvdError) as e:
+        y.plan.pull_blockwise_memcpy(y.stream.cuda_stream)
+    assert e.value.code == kvd.KVD_ERR_MISMATCH
+    y.close()
+
+
+def test_plain_copy():
+    n = (1 << 24) + 4096 + 16
+    a = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    b = torch.zeros_like(a)
+    kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr(), n)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    with pytest.raises(kvd.KvdError):
+        kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr() + 1, 16)
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+def _check_full(w, sample_layers):
+    say(f"{w.name}: allocating pools {w.src.total_bytes / 2**30:.1f} + {w.dst.total_bytes / 2**30:.1f} GiB")
+    src = G.device_random_pool(w.src, w.dtype, w.seed)
+    dst = G.device_sentinel_pool(w.dst)
+    checksum = [int(src.view(torch.int16)[i::9973][:4096].sum()) for i in range(3)]
+    x = G.GpuTransfer(w, src, dst)
+    say(f"{w.name}: build + pull")
+    x.run()
+    st = x.plan.stats(x.stream.cuda_stream)
+    say(f"{w.name}: {st}")
+    moved16 = st["payload_bytes"] // 2
+    # property on every layer: exactly the payload's words differ from the sentinel
+    sv = dst.view(torch.int16).view(w.dst.num_layers, -1)
+    nonsent = sum(int((sv[layer] != wl.SENTINEL16).sum()) for layer in range(w.dst.num_layers))
+    assert nonsent == moved16
+    # property on every layer (equal layout and block size): whole blocks arrive as whole blocks
+    if w.src.layout == w.dst.layout and w.src.block_tokens == w.dst.block_tokens:
+        s5 = src.view(torch.int16).view(w.src.num_layers, 2, w.src.num_blocks, -1)
+        d5 = dst.view(torch.int16).view(w.dst.num_layers, 2, w.dst.num_blocks, -1)
+        for r in w.requests:
+            n = r.seq_len // w.src.block_tokens
+            si = torch.from_numpy(r.src_table[:n].astype(np.int64)).cuda()
+            di = torch.from_numpy(r.dst_table[:n].astype(np.int64)).cuda()
+            for layer in range(w.layer_begin, w.layer_end):
+                assert torch.equal(d5[layer][:, di], s5[layer][:, si])
+    # oracle, element by element, on sampled layers
+    for layer in sample_layers:
+        say(f"{w.name}: oracle on layer {layer}")
+        G.compare_layer_with_oracle(w, src, dst, layer)
+    assert checksum == [int(src.view(torch.int16)[i::9973][:4096].sum()) for i in range(3)]
+    x.close()
+    del src, dst
+    torch.cuda.empty_cache()
+
+
+def test_full_config2():
+    _check_full(wl.config2(), [0, 17, 31])
+
+
+def test_full_config3():
+    _check_full(wl.config3(), [0, 31])
+
+
+def test_full_config4():
+    _check_full(wl.config4(), [0, 41, 79])
+
+
+def test_full_config5():
+    _check_full(wl.config5(), [0, 13, 31])
