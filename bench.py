@@ -166,6 +166,11 @@ def main() -> int:
         extras["no_coalesce_pull_us"] = us
         extras["no_coalesce_descriptors"] = y.plan.stats(sh)["num_descriptors"]
         y.close()
+        # the same work items walked by a persistent grid instead of one workgroup per item
+        y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_PERSISTENT, stream=stream)
+        y.build()
+        extras["persistent_grid_pull_us"] = timed(lambda: y.plan.pull(sh), 10)
+        y.close()
         # one hipMemcpyAsync per (layer, K/V, block)
         if not stats["relayout"]:
             torch.cuda.synchronize()
@@ -193,7 +198,7 @@ def main() -> int:
                    "block_tokens": [w.src.block_tokens, w.dst.block_tokens],
                    "layouts": [w.src.layout, w.dst.layout], "pool_blocks": [w.src.num_blocks, w.dst.num_blocks],
                    "payload_bytes": payload, "descriptors": stats["num_descriptors"],
-                   "transactions": stats["num_transactions"]},
+                   "transactions": stats["num_transactions"], "work_items": stats["num_work_items"]},
         "us_per_request_batch": ms_per_step * 1e3,
         "pct_of_peak": 100.0 * achieved / PEAK_HBM_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",

@@ -84,6 +84,8 @@ typedef struct kvd_plan kvd_plan_t;
 
 /* kvd_plan_create flags */
 #define KVD_PLAN_NO_COALESCE 1u /* keep every read transaction separate (ablation of section 4.2) */
+#define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a fixed grid that loops over the work items instead
+                                   of one small workgroup per work item (for comparison; slower)  */
 
 /* A coalesced read transaction of the byte-copy path, relative to (layer 0, K): the copy for
  * (layer, kv) adds layer*stride_layer*elem_bytes + kv*stride_kv*elem_bytes of the respective
@@ -106,13 +108,12 @@ typedef struct {
 
 typedef struct {
     uint32_t num_requests;
-    uint32_t num_segments;     /* descriptor groups staged one after another by the pull kernel */
     uint32_t relayout;         /* 0: byte-copy path, 1: re-layout path                           */
-    uint32_t reserved;
     uint64_t num_src_blocks;   /* table entries consumed on the source side                      */
     uint64_t num_dst_blocks;   /* table entries consumed on the destination side                 */
     uint64_t num_transactions; /* read transactions before coalescing, per (layer, kv)           */
     uint64_t num_descriptors;  /* after coalescing, per (layer, kv)                              */
+    uint64_t num_work_items;   /* 4 KiB pieces the descriptors expand to, per (layer, kv)        */
     uint64_t payload_bytes;    /* bytes one kvd_pull writes = bytes it reads                     */
 } kvd_stats_t;
 
@@ -143,7 +144,8 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
  * Append one request: Transfer() for each of its blocks (section 4.1), queued behind the
  * requests already in the plan, then coalesced with them (section 4.2: a transaction is
  * merged into its predecessor in the queue only when it continues it on both the source and
- * the destination side; merges may cross request boundaries).
+ * the destination side; merges may cross request boundaries when both requests move the same
+ * layers).
  *
  * src_block_table[n_src], dst_block_table[n_dst]: HOST arrays of physical block ids in
  * logical order; token t of the request is in source block src_block_table[t / Tsrc] slot
@@ -169,8 +171,9 @@ int kvd_build_descriptors(kvd_plan_t *plan, const int32_t *src_block_table, uint
 /*
  * Issue every queued (merged or unmerged) read of the plan at once, for all its requests,
  * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
- * blocking; section 4.3: all layers in a single shot).  May be called repeatedly; a plan with
- * no requests is a no-op.  Completion (section 4.1, Complete()) is the caller's
+ * blocking; section 4.3: all layers in a single shot).  Every read is cut into work items of at
+ * most 4 KiB and each (work item, layer, K/V) is moved by its own small workgroup, 16 bytes per
+ * lane.  May be called repeatedly; a plan with no requests is a no-op.  Completion (section 4.1, Complete()) is the caller's
  * synchronisation on `stream`.
  * Errors: KVD_ERR_INVALID, KVD_ERR_HIP.
  */

@@ -1,15 +1,21 @@
 // kvd - paged KV-cache pull for MI355X (gfx950): kernels and C ABI.
 //
 // Data path of KVDirect (arXiv 2501.14743), sections 4.1-4.3, with both pools in one GPU's
-// HBM.  Three kernels:
-//   kvd_build_kernel   block ids -> byte ranges (section 4.1) and coalescing of queued ranges
-//                      (section 4.2) with a wave64 ballot + prefix scan; one workgroup.
-//   kvd_pull_kernel    persistent grid; stages the coalesced descriptors in LDS and moves
-//                      16 bytes per lane per access for every (layer, K/V) slab.
+// HBM.  Kernels:
+//   kvd_build_kernel   one workgroup per appended request: block ids -> byte ranges (section
+//                      4.1), coalescing of queued ranges with a wave64 ballot + prefix scan
+//                      (section 4.2), then expansion of the coalesced ranges into a table of
+//                      fixed 4 KiB work items.
+//   kvd_pull_kernel    moves the bytes: one small workgroup per (work item, layer, K/V), one
+//                      16-byte load and one 16-byte store per lane, non-temporal.  The
+//                      hardware dispatcher hands the work items out in table order, which
+//                      keeps the traffic an orderly sweep; measured on MI355X this beats a
+//                      persistent grid that loops over the same items.
+//   kvd_pull_loop_kernel  the persistent-grid form of the same copy (kept for comparison).
 //   kvd_copy_kernel    plain streaming copy (counter calibration / practical ceiling).
 //
-// A descriptor is relative to the (layer 0, K) slab; the pull kernel adds the slab offset of
-// each side, so one descriptor list serves every layer and both K and V (the receiver
+// Descriptors and work items are relative to the (layer 0, K) slab; the pull kernel adds the
+// slab offset of each side, so one list serves every layer and both K and V (the receiver
 // computes locations from the tensor metadata, section 4.1).
 
 #include <hip/hip_runtime.h>
@@ -25,11 +31,9 @@
 
 namespace {
 
-constexpr uint32_t kUnitBytes = 16;     // one lane moves 16 bytes per access
-constexpr uint32_t kChunkUnits = 256;   // one wave step: 64 lanes x 4 accesses = 4 KiB
-constexpr uint32_t kSegCap = 4096;      // descriptors per segment (LDS: 16 B each = 64 KiB)
+constexpr uint32_t kUnitBytes = 16;    // one lane moves 16 bytes per access
+constexpr uint32_t kChunkUnits = 256;  // work item: at most 256 units = 4 KiB
 constexpr uint32_t kBuildThreads = 1024;
-constexpr uint32_t kPullThreads = 1024;
 constexpr uint32_t kWave = 64;
 
 enum Mode : uint32_t {
@@ -39,21 +43,31 @@ enum Mode : uint32_t {
     kRelayoutTH2HT = 3    // source [token][head][dim] -> destination [head][token][dim]
 };
 
-// 16 bytes.  Offsets and lengths count 16-byte units.
+// Coalesced read transaction, 16 bytes.  Offsets and lengths count 16-byte units.
 //   byte-copy path: a = first unit past the end on the source side (length = a - src16)
 //   re-layout path: a = src_token | dst_token << 10 | num_tokens << 20; src16/dst16 = block base
 struct Desc {
     uint32_t src16;
     uint32_t dst16;
     uint32_t a;
-    uint32_t prefix;  // 4 KiB wave steps needed by all earlier descriptors of the segment
+    uint32_t prefix;  // work items needed by all earlier descriptors
 };
 
-struct SegHeader {
+// Work item, 16 bytes: what the pull kernel moves per (layer, K/V) for one table entry.
+//   byte-copy path: n = units (1..256) starting at src16 / dst16
+//   re-layout path: n = first_row | (rows - 1) << 20, rows of one (token, head) each, numbered
+//                   token-major inside the piece; src16 / dst16 = the piece's first token
+//   layers = layer_begin | num_layers << 16; 0 marks an unused entry
+struct Item {
+    uint32_t src16;
+    uint32_t dst16;
+    uint32_t n;
+    uint32_t layers;
+};
+
+struct Header {
     uint32_t n_desc;
-    uint32_t n_chunks;
-    uint32_t layer_begin;
-    uint32_t layer_end;
+    uint32_t n_items;
 };
 
 // Exact unsigned division by a run-time constant through multiply-high and shifts
@@ -85,22 +99,26 @@ struct Geo {
     uint32_t tb_src, tb_dst;            // tokens per block
     uint32_t hk, du;                    // KV heads; 16-byte units per (token, head) row
     uint32_t piece_tokens;              // min(tb_src, tb_dst): tokens that share a block on both sides
+    uint32_t rows_per_item;             // re-layout: (token, head) rows per work item = 256 / du
     uint32_t mode;
-    FastDiv div_du, div_hkdu, div_piecedu, div_tb_src, div_tb_dst;
+    FastDiv div_du, div_hk, div_tb_src, div_tb_dst;
 };
 
-// ------------------------------------------------------------------ build: translate + coalesce
+// ------------------------------------------------------------------ build: translate + coalesce + expand
 
 struct BuildArgs {
     const int32_t *src_table;  // this request's tables (device-visible pinned host memory)
     const int32_t *dst_table;
-    Desc *desc;                // the segment's descriptor array
-    SegHeader *seg;
+    Desc *desc;
+    Item *items;
+    Header *hdr;
     uint32_t seq_len;
-    uint32_t j_begin, j_end;   // transactions of this request that go into this segment
+    uint32_t n_txn;            // read transactions of this request per (layer, K/V)
     uint32_t n_single;         // head-major, equal block size: leading whole-block transactions
-    uint32_t layer_begin, layer_end;
-    uint32_t fresh;            // 1: the segment is empty (header contents are stale)
+    uint32_t layers;           // layer_begin | num_layers << 16
+    uint32_t item_bound;       // entries [n_items, item_bound) of the table are cleared
+    uint32_t fresh;            // 1: the plan is empty (header contents are stale)
+    uint32_t may_merge_prev;   // 1: the previous request moves the same layers
     uint32_t no_coalesce;
 };
 
@@ -124,7 +142,7 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, uint32
                 per_head = true;
             }
         } else {
-            piece = j / g.hk;
+            piece = fdiv(j, g.div_hk);
             head = j - piece * g.hk;
             per_head = true;
         }
@@ -162,10 +180,10 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, uint32
     return t;
 }
 
-__device__ __forceinline__ uint32_t desc_chunks(const Geo &g, const Desc &d)
+__device__ __forceinline__ uint32_t desc_items(const Geo &g, const Desc &d)
 {
-    uint32_t units = (g.mode >= kRelayoutHT2TH) ? (d.a >> 20) * g.hk * g.du : d.a - d.src16;
-    return (units + kChunkUnits - 1) / kChunkUnits;
+    if (g.mode >= kRelayoutHT2TH) return ((d.a >> 20) * g.hk + g.rows_per_item - 1) / g.rows_per_item;
+    return (d.a - d.src16 + kChunkUnits - 1) / kChunkUnits;
 }
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildArgs a)
@@ -178,13 +196,13 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const bool relayout = g.mode >= kRelayoutHT2TH;
     const bool never_merge = relayout || a.no_coalesce;
-    const uint32_t n0 = a.fresh ? 0u : a.seg->n_desc;
+    const uint32_t n0 = a.fresh ? 0u : a.hdr->n_desc;
 
     // The queue's last transaction so far: a new transaction that continues it on both sides
     // is merged into it, also when it belongs to another request (section 4.2).
     bool have_prev = false;
     uint32_t prev_s = 0, prev_d = 0;
-    if (n0 > 0 && !never_merge) {
+    if (n0 > 0 && !never_merge && a.may_merge_prev) {
         Desc p = a.desc[n0 - 1];
         have_prev = true;
         prev_s = p.a;
@@ -193,9 +211,9 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     const bool had_open = have_prev;
     uint32_t runs = n0;
 
-    for (uint32_t tile = a.j_begin; tile < a.j_end; tile += kBuildThreads) {
+    for (uint32_t tile = 0; tile < a.n_txn; tile += kBuildThreads) {
         const uint32_t j = tile + tid;
-        const bool valid = j < a.j_end;
+        const bool valid = j < a.n_txn;
         Txn t = {0, 0, 0, 0};
         if (valid) t = make_txn(g, a, j);
         s_end_s[tid] = t.s16 + t.len16;
@@ -208,7 +226,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             pd = s_end_d[tid - 1];
             hp = true;
         }
-        const uint32_t tile_last = min(kBuildThreads, a.j_end - tile) - 1;
+        const uint32_t tile_last = min(kBuildThreads, a.n_txn - tile) - 1;
         const uint32_t next_prev_s = s_end_s[tile_last], next_prev_d = s_end_d[tile_last];
 
         // break flag: this transaction starts a new descriptor
@@ -245,20 +263,21 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         __syncthreads();
     }
 
-    // chunk prefix over the descriptors that are new or were extended
+    // work-item prefix over the descriptors that are new or were extended
     const uint32_t n1 = runs;
     const uint32_t from = had_open ? n0 - 1 : n0;
-    uint32_t carry = 0;
+    uint32_t first_item = 0;
     if (from > 0) {
         Desc p = a.desc[from - 1];
-        carry = p.prefix + desc_chunks(g, p);
+        first_item = p.prefix + desc_items(g, p);
     }
+    uint32_t carry = first_item;
     for (uint32_t base = from; base < n1; base += kBuildThreads) {
         const uint32_t i = base + tid;
         const bool v = i < n1;
         Desc d = {0, 0, 0, 0};
         if (v) d = a.desc[i];
-        const uint32_t c = v ? desc_chunks(g, d) : 0u;
+        const uint32_t c = v ? desc_items(g, d) : 0u;
         uint32_t incl = c;  // inclusive scan inside the wave
 #pragma unroll
         for (uint32_t o = 1; o < kWave; o <<= 1) {
@@ -278,11 +297,41 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         carry += total;
         __syncthreads();
     }
+    const uint32_t n_items = carry;
+
+    // expand descriptors [from, n1) into work items [first_item, n_items); clear up to the bound
+    for (uint32_t c = first_item + tid; c < a.item_bound; c += kBuildThreads) {
+        Item it = {0, 0, 0, 0};
+        if (c < n_items) {
+            uint32_t lo = from, hi = n1;  // largest i with prefix[i] <= c
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (a.desc[mid].prefix <= c) lo = mid; else hi = mid;
+            }
+            const Desc d = a.desc[lo];
+            const uint32_t cl = c - d.prefix;
+            it.layers = a.layers;
+            if (!relayout) {
+                it.src16 = d.src16 + cl * kChunkUnits;
+                it.dst16 = d.dst16 + cl * kChunkUnits;
+                it.n = min(kChunkUnits, d.a - d.src16 - cl * kChunkUnits);
+            } else {
+                const uint32_t st0 = d.a & 1023u, dt0 = (d.a >> 10) & 1023u, ntok = d.a >> 20;
+                const uint32_t row0 = cl * g.rows_per_item;
+                const uint32_t rows = min(g.rows_per_item, ntok * g.hk - row0);
+                // fold the first token's slot into the bases (both layouts are linear in the slot)
+                const uint32_t s_tok = (g.mode == kRelayoutHT2TH) ? g.du : g.hk * g.du;
+                const uint32_t d_tok = (g.mode == kRelayoutHT2TH) ? g.hk * g.du : g.du;
+                it.src16 = d.src16 + st0 * s_tok;
+                it.dst16 = d.dst16 + dt0 * d_tok;
+                it.n = row0 | ((rows - 1) << 20);
+            }
+        }
+        a.items[c] = it;
+    }
     if (tid == 0) {
-        a.seg->n_desc = n1;
-        a.seg->n_chunks = carry;
-        a.seg->layer_begin = a.layer_begin;
-        a.seg->layer_end = a.layer_end;
+        a.hdr->n_desc = n1;
+        a.hdr->n_items = n_items;
     }
 }
 
@@ -293,146 +342,65 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct PullArgs {
     const unsigned char *src_base;
     unsigned char *dst_base;
-    const Desc *desc;       // n_segments arrays of kSegCap descriptors
-    const SegHeader *segs;
-    uint32_t n_segments;
-    uint32_t lds_cap;       // descriptors the dynamic LDS can hold
+    const Item *items;
+    uint32_t n_items;  // table entries to visit (unused ones are skipped)
+    uint32_t slabs;    // 2 * the largest layer count of any request
 };
 
-__device__ __forceinline__ uint32_t find_desc(const uint32_t *l_prefix, uint32_t n, uint32_t c)
+// One 16-byte unit of work item `it` for slab `y` (= 2 * layer offset + kv): lane unit u.
+__device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const Item it, uint32_t y,
+                                          uint32_t u)
 {
-    // largest i with prefix[i] <= c
-    uint32_t lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (l_prefix[mid] <= c) lo = mid; else hi = mid;
+    if (y >= (it.layers >> 16) * 2) return;
+    uint32_t s16, d16;
+    if (g.mode < kRelayoutHT2TH) {
+        if (u >= it.n) return;
+        s16 = it.src16 + u;
+        d16 = it.dst16 + u;
+    } else {
+        const uint32_t r = fdiv(u, g.div_du), x = u - r * g.du;
+        if (r > (it.n >> 20)) return;
+        const uint32_t row = (it.n & 0xFFFFFu) + r;
+        const uint32_t tok = fdiv(row, g.div_hk), head = row - tok * g.hk;
+        const uint32_t in_ht_src = head * g.tb_src + tok, in_ht_dst = head * g.tb_dst + tok;
+        s16 = it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
+        d16 = it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
     }
-    return lo;
+    const uint32_t layer = (it.layers & 0xFFFFu) + (y >> 1), kv = y & 1u;
+    const unsigned char *sp = a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
+    unsigned char *dp = a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(sp + (size_t)s16 * kUnitBytes));
+    __builtin_nontemporal_store(v, (u32x4 *)(dp + (size_t)d16 * kUnitBytes));
 }
 
-__global__ __launch_bounds__(kPullThreads) void kvd_pull_kernel(Geo g, PullArgs a)
+// grid = (n_items * 256 / T, slabs): workgroup x handles T consecutive units of item x / (256 / T).
+template <int T>
+__global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
 {
-    extern __shared__ uint32_t lds[];
-    uint32_t *l_prefix = lds;
-    uint32_t *l_src = lds + a.lds_cap;
-    uint32_t *l_dst = lds + 2 * a.lds_cap;
-    uint32_t *l_a = lds + 3 * a.lds_cap;
+    constexpr uint32_t kParts = kChunkUnits / T;
+    const uint32_t c = blockIdx.x / kParts, part = blockIdx.x % kParts;
+    const Item it = a.items[c];
+    move_unit(g, a, it, blockIdx.y, part * T + threadIdx.x);
+}
 
-    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
-    const uint32_t waves_per_block = blockDim.x / kWave;
-    const uint32_t W = blockIdx.x * waves_per_block + tid / kWave;
-    const uint32_t NW = gridDim.x * waves_per_block;
-    const bool relayout = g.mode >= kRelayoutHT2TH;
-
-    for (uint32_t s = 0; s < a.n_segments; ++s) {
-        const SegHeader h = a.segs[s];
-        const Desc *d = a.desc + (size_t)s * kSegCap;
-        __syncthreads();
-        for (uint32_t i = tid; i < h.n_desc; i += blockDim.x) {
-            const Desc x = d[i];
-            l_prefix[i] = x.prefix;
-            l_src[i] = x.src16;
-            l_dst[i] = x.dst16;
-            l_a[i] = relayout ? x.a : x.a - x.src16;
-        }
-        __syncthreads();
-
-        const uint32_t slabs = (h.layer_end - h.layer_begin) * 2;
-        const uint32_t nc = h.n_chunks;
-        if (nc == 0 || slabs == 0) continue;
-        const uint32_t full_rounds = nc / NW;
-        const uint32_t rem = nc - full_rounds * NW;
-        // Rounds 0..full_rounds-1: wave W takes chunk r*NW + W through every slab.  Last round:
-        // the remaining chunks are spread over all waves by also splitting the slabs.
-        for (uint32_t r = 0; r <= full_rounds; ++r) {
-            uint32_t c, slab0, slab_step;
-            if (r < full_rounds) {
-                c = r * NW + W;
-                slab0 = 0;
-                slab_step = 1;
-            } else {
-                if (rem == 0) break;
-                const uint32_t phases = min(NW / rem, slabs);
-                if (W >= rem * phases) break;
-                slab0 = W / rem;
-                c = full_rounds * NW + (W - slab0 * rem);
-                slab_step = phases;
-            }
-            const uint32_t i = find_desc(l_prefix, h.n_desc, c);
-            const uint32_t cl = c - l_prefix[i];
-            uint32_t s_off[4], d_off[4];
-            bool ok[4];
-            if (!relayout) {
-                const uint32_t left = l_a[i] - cl * kChunkUnits;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t u = k * kWave + lane;
-                    ok[k] = u < left;
-                    s_off[k] = l_src[i] + cl * kChunkUnits + u;
-                    d_off[k] = l_dst[i] + cl * kChunkUnits + u;
-                }
-            } else {
-                const uint32_t meta = l_a[i];
-                const uint32_t st0 = meta & 1023u, dt0 = (meta >> 10) & 1023u, ntok = meta >> 20;
-                const uint32_t units = ntok * g.hk * g.du;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t u = cl * kChunkUnits + k * kWave + lane;
-                    ok[k] = u < units;
-                    uint32_t tok, head, x;
-                    if (g.mode == kRelayoutHT2TH) {
-                        // destination order: token, head, dim
-                        tok = fdiv(u, g.div_hkdu);
-                        const uint32_t r2 = u - tok * g.hk * g.du;
-                        head = fdiv(r2, g.div_du);
-                        x = r2 - head * g.du;
-                        s_off[k] = l_src[i] + (head * g.tb_src + st0 + tok) * g.du + x;
-                        d_off[k] = l_dst[i] + ((dt0 + tok) * g.hk + head) * g.du + x;
-                    } else {
-                        // destination order: head, token, dim
-                        head = (ntok == g.piece_tokens) ? fdiv(u, g.div_piecedu) : u / (ntok * g.du);
-                        const uint32_t r2 = u - head * ntok * g.du;
-                        tok = fdiv(r2, g.div_du);
-                        x = r2 - tok * g.du;
-                        s_off[k] = l_src[i] + ((st0 + tok) * g.hk + head) * g.du + x;
-                        d_off[k] = l_dst[i] + (head * g.tb_dst + dt0 + tok) * g.du + x;
-                    }
-                }
-            }
-            for (uint32_t slab = slab0; slab < slabs; slab += slab_step) {
-                const uint32_t layer = h.layer_begin + (slab >> 1), kv = slab & 1u;
-                const unsigned char *sp = a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
-                unsigned char *dp = a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
-                u32x4 v[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (ok[k]) v[k] = *(const u32x4 *)(sp + (size_t)s_off[k] * kUnitBytes);
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (ok[k]) *(u32x4 *)(dp + (size_t)d_off[k] * kUnitBytes) = v[k];
-            }
-        }
+// Persistent form: a fixed grid walks the same (slab, item) space in the same order.
+template <int T>
+__global__ __launch_bounds__(T) void kvd_pull_loop_kernel(Geo g, PullArgs a)
+{
+    constexpr uint32_t kParts = kChunkUnits / T;
+    const uint64_t per_slab = (uint64_t)a.n_items * kParts, total = per_slab * a.slabs;
+    for (uint64_t w = blockIdx.x; w < total; w += gridDim.x) {
+        const uint32_t y = (uint32_t)(w / per_slab), x = (uint32_t)(w - y * per_slab);
+        const Item it = a.items[x / kParts];
+        move_unit(g, a, it, y, (x % kParts) * T + threadIdx.x);
     }
 }
 
 __global__ __launch_bounds__(256) void kvd_copy_kernel(u32x4 *__restrict__ dst,
                                                        const u32x4 *__restrict__ src, uint64_t units)
 {
-    // every workgroup step moves 256 lanes x 4 x 16 B = 16 KiB, grid-stride
-    const uint64_t step = (uint64_t)gridDim.x * 1024;
-    for (uint64_t base = (uint64_t)blockIdx.x * 1024; base < units; base += step) {
-        u32x4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint64_t u = base + k * 256 + threadIdx.x;
-            if (u < units) v[k] = src[u];
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint64_t u = base + k * 256 + threadIdx.x;
-            if (u < units) dst[u] = v[k];
-        }
-    }
+    const uint64_t u = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (u < units) __builtin_nontemporal_store(__builtin_nontemporal_load(src + u), dst + u);
 }
 
 // ------------------------------------------------------------------ host side
@@ -458,11 +426,6 @@ int fail(int code, const char *fmt, ...)
 constexpr uint32_t kPoolTag = 0x6b76504fu;  // handle type tags
 constexpr uint32_t kPlanTag = 0x6b76504cu;
 
-struct SegHost {
-    uint32_t txns;
-    uint32_t layer_begin, layer_end;
-};
-
 struct ReqHost {
     uint32_t table_off_src, table_off_dst;  // into the plan's table mirrors
     uint32_t n_src, n_dst;                  // entries used
@@ -482,13 +445,12 @@ struct kvd_plan {
     kvd_pool_desc_t src, dst;
     uint32_t max_requests, max_total_blocks, flags;
     Geo geo;
-    uint64_t max_txns;
-    uint32_t max_segments;
+    uint64_t max_txns, max_items;
     // host bookkeeping
     std::vector<ReqHost> reqs;
-    std::vector<SegHost> segs;
     std::vector<uint8_t> dst_used;  // one byte per destination block
-    uint64_t used_src, used_dst, txns_total, payload_bytes;
+    uint64_t used_src, used_dst, txns_total, item_bound, payload_bytes;
+    uint32_t max_layers;            // largest layer count of any request in the plan
     // device / pinned scratch (allocated on first use)
     bool allocated;
     int device;
@@ -496,7 +458,8 @@ struct kvd_plan {
     int32_t *tables_src, *tables_dst;  // pinned host, device-visible
     int32_t *tables_src_dev, *tables_dst_dev;
     Desc *desc_dev;
-    SegHeader *segs_dev;
+    Item *items_dev;
+    Header *hdr_dev;
     hipEvent_t build_done;
     bool build_pending;
 };
@@ -513,6 +476,7 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
     if (d.layout != KVD_LAYOUT_BHTD && d.layout != KVD_LAYOUT_BTHD)
         return fail(KVD_ERR_INVALID, "unknown layout %d", d.layout);
     if (d.block_tokens > 1024) return fail(KVD_ERR_INVALID, "block_tokens above 1024");
+    if (d.num_layers > 32767) return fail(KVD_ERR_INVALID, "num_layers above 32767");
     if (d.stride_layer < 0 || d.stride_kv < 0 || d.stride_block < 0)
         return fail(KVD_ERR_INVALID, "negative stride");
     const uint64_t e = d.elem_bytes;
@@ -523,6 +487,10 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
         ((uint64_t)d.stride_kv * e % 16) || ((uint64_t)d.stride_block * e % 16) ||
         ((uint64_t)d.head_dim * e % 16))
         return fail(KVD_ERR_INVALID, "base, strides and head_dim*elem_bytes must be multiples of 16 bytes");
+    if ((uint64_t)d.head_dim * e > 4096)
+        return fail(KVD_ERR_INVALID, "head_dim*elem_bytes above 4096 bytes");
+    if ((uint64_t)d.block_tokens * d.num_kv_heads > (1u << 20))
+        return fail(KVD_ERR_INVALID, "block_tokens*num_kv_heads above 2^20");
     const uint64_t block_axis = ((uint64_t)(d.num_blocks - 1) * d.stride_block + tile) * e;
     if (block_axis >= (1ull << 36))
         return fail(KVD_ERR_RANGE, "block axis of one slab spans more than 64 GiB");
@@ -532,16 +500,31 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
 
 uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
-// number of read transactions of one request per (layer, kv), and the leading whole-block ones
-uint32_t request_txns(const Geo &g, uint32_t seq_len, uint32_t *n_single)
+// Sizes of one request per (layer, kv): read transactions, the leading whole-block ones, and
+// the work items they need before any merging (an upper bound of the number after merging).
+void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *n_single, uint32_t *items)
 {
     const uint32_t pieces = ceil_div(seq_len, g.piece_tokens);
+    const uint32_t whole = seq_len / g.piece_tokens, tail = seq_len % g.piece_tokens;
     *n_single = 0;
-    if (g.mode != kSpanHeadMajor) return pieces;
-    if (g.tb_src != g.tb_dst) return pieces * g.hk;
-    const uint32_t whole = seq_len / g.tb_src;
-    *n_single = whole;
-    return whole + ((seq_len % g.tb_src) ? g.hk : 0);
+    if (g.mode >= kRelayoutHT2TH) {
+        *n_txn = pieces;
+        *items = whole * ceil_div(g.piece_tokens * g.hk, g.rows_per_item) +
+                 (tail ? ceil_div(tail * g.hk, g.rows_per_item) : 0);
+    } else if (g.mode == kSpanTokenMajor) {
+        *n_txn = pieces;
+        *items = whole * ceil_div(g.piece_tokens * g.hk * g.du, kChunkUnits) +
+                 (tail ? ceil_div(tail * g.hk * g.du, kChunkUnits) : 0);
+    } else if (g.tb_src != g.tb_dst) {
+        *n_txn = pieces * g.hk;
+        *items = g.hk * (whole * ceil_div(g.piece_tokens * g.du, kChunkUnits) +
+                         (tail ? ceil_div(tail * g.du, kChunkUnits) : 0));
+    } else {
+        *n_single = whole;
+        *n_txn = whole + (tail ? g.hk : 0);
+        *items = whole * ceil_div(g.piece_tokens * g.hk * g.du, kChunkUnits) +
+                 (tail ? g.hk * ceil_div(tail * g.du, kChunkUnits) : 0);
+    }
 }
 
 int ensure_allocated(kvd_plan *p)
@@ -556,9 +539,9 @@ int ensure_allocated(kvd_plan *p)
     KVD_HIP(hipHostMalloc((void **)&p->tables_dst, tb, hipHostMallocMapped));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->tables_src_dev, p->tables_src, 0));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->tables_dst_dev, p->tables_dst, 0));
-    KVD_HIP(hipMalloc((void **)&p->desc_dev, (size_t)p->max_segments * kSegCap * sizeof(Desc)));
-    KVD_HIP(hipMalloc((void **)&p->segs_dev, (size_t)p->max_segments * sizeof(SegHeader)));
-    KVD_HIP(hipMemset(p->segs_dev, 0, (size_t)p->max_segments * sizeof(SegHeader)));
+    KVD_HIP(hipMalloc((void **)&p->desc_dev, (size_t)p->max_txns * sizeof(Desc)));
+    KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
+    KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
     KVD_HIP(hipEventCreateWithFlags(&p->build_done, hipEventDisableTiming));
     p->allocated = true;
     return KVD_OK;
@@ -571,7 +554,8 @@ void release_plan(kvd_plan *p)
         (void)hipHostFree(p->tables_src);
         (void)hipHostFree(p->tables_dst);
         (void)hipFree(p->desc_dev);
-        (void)hipFree(p->segs_dev);
+        (void)hipFree(p->items_dev);
+        (void)hipFree(p->hdr_dev);
         (void)hipEventDestroy(p->build_done);
     }
     p->tag = 0;
@@ -646,24 +630,32 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     g.hk = s.num_kv_heads;
     g.du = (uint32_t)((uint64_t)s.head_dim * e / kUnitBytes);
     g.piece_tokens = tmin;
+    g.rows_per_item = kChunkUnits / g.du;
     if (s.layout == d.layout || g.hk == 1)
         g.mode = (s.layout == KVD_LAYOUT_BTHD || g.hk == 1) ? kSpanTokenMajor : kSpanHeadMajor;
     else
         g.mode = (s.layout == KVD_LAYOUT_BHTD) ? kRelayoutHT2TH : kRelayoutTH2HT;
     g.div_du = make_fastdiv(g.du);
-    g.div_hkdu = make_fastdiv(g.hk * g.du);
-    g.div_piecedu = make_fastdiv(g.piece_tokens * g.du);
+    g.div_hk = make_fastdiv(g.hk);
     g.div_tb_src = make_fastdiv(g.tb_src);
     g.div_tb_dst = make_fastdiv(g.tb_dst);
 
-    // upper bound of transactions the plan can hold -> number of descriptor segments
+    // upper bounds of what the plan can hold: read transactions and work items
     const uint64_t pieces_max = (uint64_t)max_total_blocks * (tmax / tmin);
     if (g.mode == kSpanHeadMajor)
         p->max_txns = (g.tb_src == g.tb_dst) ? pieces_max + (uint64_t)max_requests * g.hk
                                              : pieces_max * g.hk;
     else
         p->max_txns = pieces_max;
-    p->max_segments = (uint32_t)((p->max_txns + kSegCap - 1) / kSegCap) + max_requests;
+    const uint64_t units_max = pieces_max * tmin * g.hk * g.du;
+    if (g.mode >= kRelayoutHT2TH)
+        p->max_items = pieces_max * tmin * g.hk / g.rows_per_item + p->max_txns + 1;
+    else
+        p->max_items = units_max / kChunkUnits + p->max_txns + 1;
+    if (p->max_items >= (1ull << 31) || p->max_txns >= (1ull << 31)) {
+        delete p;
+        return fail(KVD_ERR_CAPACITY, "plan capacity too large");
+    }
     p->dst_used.assign(d.num_blocks, 0);
     p->reqs.reserve(max_requests);
     p->allocated = false;
@@ -683,8 +675,8 @@ int kvd_plan_reset(kvd_plan_t *p)
         for (uint32_t i = 0; i < r.n_dst; ++i)
             p->dst_used[(uint32_t)p->tables_dst[r.table_off_dst + i]] = 0;
     p->reqs.clear();
-    p->segs.clear();
-    p->used_src = p->used_dst = p->txns_total = p->payload_bytes = 0;
+    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = 0;
+    p->max_layers = 0;
     return KVD_OK;
 }
 
@@ -709,24 +701,36 @@ int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
     for (uint32_t i = 0; i < need_dst; ++i)
         if (dst_tbl[i] < 0 || (uint32_t)dst_tbl[i] >= p->dst.num_blocks)
             return fail(KVD_ERR_RANGE, "destination block id %d at entry %u outside [0, %u)", dst_tbl[i], i, p->dst.num_blocks);
-    // every destination byte is written at most once per plan
+    // every destination byte is written at most once per plan: 2 marks this request's blocks
+    // until the call is sure to succeed, 1 marks blocks of accepted requests
+    auto unmark = [&](uint32_t upto) {
+        for (uint32_t k = 0; k < upto; ++k)
+            if (p->dst_used[(uint32_t)dst_tbl[k]] == 2) p->dst_used[(uint32_t)dst_tbl[k]] = 0;
+    };
     for (uint32_t i = 0; i < need_dst; ++i) {
         uint8_t &u = p->dst_used[(uint32_t)dst_tbl[i]];
         if (u) {
-            for (uint32_t k = 0; k < i; ++k)  // undo this request's marks; earlier requests keep theirs
-                if (p->dst_used[(uint32_t)dst_tbl[k]] == 2) p->dst_used[(uint32_t)dst_tbl[k]] = 0;
+            unmark(i);
             return fail(KVD_ERR_ALIAS, "destination block %d (entry %u) is already a target in this plan", dst_tbl[i], i);
         }
         u = 2;
     }
-    auto unmark = [&]() { for (uint32_t i = 0; i < need_dst; ++i) p->dst_used[(uint32_t)dst_tbl[i]] = 0; };
-    if (p->reqs.size() >= p->max_requests) { unmark(); return fail(KVD_ERR_CAPACITY, "plan already holds %u requests", p->max_requests); }
-    if (p->used_src + need_src > p->max_total_blocks || p->used_dst + need_dst > p->max_total_blocks) {
-        unmark();
+    uint32_t n_txn = 0, n_single = 0, items = 0;
+    request_sizes(g, seq_len, &n_txn, &n_single, &items);
+    if (p->reqs.size() >= p->max_requests) {
+        unmark(need_dst);
+        return fail(KVD_ERR_CAPACITY, "plan already holds %u requests", p->max_requests);
+    }
+    if (p->used_src + need_src > p->max_total_blocks || p->used_dst + need_dst > p->max_total_blocks ||
+        p->txns_total + n_txn > p->max_txns || p->item_bound + items > p->max_items) {
+        unmark(need_dst);
         return fail(KVD_ERR_CAPACITY, "plan holds at most %u block-table entries per side", p->max_total_blocks);
     }
     int rc = ensure_allocated(p);
-    if (rc != KVD_OK) { unmark(); return rc; }
+    if (rc != KVD_OK) {
+        unmark(need_dst);
+        return rc;
+    }
     for (uint32_t i = 0; i < need_dst; ++i) p->dst_used[(uint32_t)dst_tbl[i]] = 1;
 
     ReqHost r;
@@ -739,66 +743,63 @@ int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
     r.layer_end = layer_end;
     memcpy(p->tables_src + r.table_off_src, src_tbl, (size_t)need_src * sizeof(int32_t));
     memcpy(p->tables_dst + r.table_off_dst, dst_tbl, (size_t)need_dst * sizeof(int32_t));
+    const bool fresh = p->reqs.empty();
+    const bool same_layers = !fresh && p->reqs.back().layer_begin == layer_begin &&
+                             p->reqs.back().layer_end == layer_end;
+
+    BuildArgs a;
+    a.src_table = p->tables_src_dev + r.table_off_src;
+    a.dst_table = p->tables_dst_dev + r.table_off_dst;
+    a.desc = p->desc_dev;
+    a.items = p->items_dev;
+    a.hdr = p->hdr_dev;
+    a.seq_len = seq_len;
+    a.n_txn = n_txn;
+    a.n_single = n_single;
+    a.layers = layer_begin | ((layer_end - layer_begin) << 16);
+    a.item_bound = (uint32_t)(p->item_bound + items);
+    a.fresh = fresh ? 1u : 0u;
+    a.may_merge_prev = same_layers ? 1u : 0u;
+    a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
+    hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
+    hipError_t launch = hipGetLastError();
+    if (launch == hipSuccess) launch = hipEventRecord(p->build_done, (hipStream_t)stream);
+    if (launch != hipSuccess) {
+        for (uint32_t i = 0; i < need_dst; ++i) p->dst_used[(uint32_t)dst_tbl[i]] = 0;
+        return fail(KVD_ERR_HIP, "launch of the build kernel failed: %s", hipGetErrorString(launch));
+    }
+    p->build_pending = true;
+
     p->used_src += need_src;
     p->used_dst += need_dst;
-    p->reqs.push_back(r);
+    p->txns_total += n_txn;
+    p->item_bound += items;
+    p->max_layers = std::max(p->max_layers, layer_end - layer_begin);
     p->payload_bytes += (uint64_t)seq_len * (layer_end - layer_begin) * 2 * g.hk * g.du * kUnitBytes;
-
-    uint32_t n_single = 0;
-    const uint32_t m = request_txns(g, seq_len, &n_single);
-    p->txns_total += m;
-    uint32_t j = 0;
-    while (j < m) {
-        bool fresh = false;
-        if (p->segs.empty() || p->segs.back().txns == kSegCap ||
-            p->segs.back().layer_begin != layer_begin || p->segs.back().layer_end != layer_end) {
-            if (p->segs.size() >= p->max_segments) return fail(KVD_ERR_CAPACITY, "plan is out of descriptor segments");
-            p->segs.push_back(SegHost{0, layer_begin, layer_end});
-            fresh = true;
-        }
-        SegHost &sh = p->segs.back();
-        const uint32_t take = std::min(m - j, kSegCap - sh.txns);
-        const size_t si = p->segs.size() - 1;
-        BuildArgs a;
-        a.src_table = p->tables_src_dev + r.table_off_src;
-        a.dst_table = p->tables_dst_dev + r.table_off_dst;
-        a.desc = p->desc_dev + si * kSegCap;
-        a.seg = p->segs_dev + si;
-        a.seq_len = seq_len;
-        a.j_begin = j;
-        a.j_end = j + take;
-        a.n_single = n_single;
-        a.layer_begin = layer_begin;
-        a.layer_end = layer_end;
-        a.fresh = fresh ? 1u : 0u;
-        a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
-        hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
-        KVD_HIP(hipGetLastError());
-        sh.txns += take;
-        j += take;
-    }
-    KVD_HIP(hipEventRecord(p->build_done, (hipStream_t)stream));
-    p->build_pending = true;
+    p->reqs.push_back(r);
     return KVD_OK;
 }
 
 int kvd_pull(kvd_plan_t *p, void *stream)
 {
     if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
-    if (p->segs.empty()) return KVD_OK;
-    uint32_t lds_cap = 0;
-    for (const SegHost &s : p->segs) lds_cap = std::max(lds_cap, s.txns);
-    lds_cap = (lds_cap + 63u) & ~63u;
+    if (p->reqs.empty()) return KVD_OK;
     PullArgs a;
     a.src_base = (const unsigned char *)p->src.base;
     a.dst_base = (unsigned char *)p->dst.base;
-    a.desc = p->desc_dev;
-    a.segs = p->segs_dev;
-    a.n_segments = (uint32_t)p->segs.size();
-    a.lds_cap = lds_cap;
-    const uint32_t grid = (uint32_t)p->num_cus * 2;  // persistent: two 1024-thread workgroups per CU
-    hipLaunchKernelGGL(kvd_pull_kernel, dim3(grid), dim3(kPullThreads), (size_t)lds_cap * 16,
-                       (hipStream_t)stream, p->geo, a);
+    a.items = p->items_dev;
+    a.n_items = (uint32_t)p->item_bound;
+    a.slabs = p->max_layers * 2;
+    constexpr int T = 64;
+    if (p->flags & KVD_PLAN_PERSISTENT) {
+        const uint32_t grid = (uint32_t)p->num_cus * (2048 / T);
+        hipLaunchKernelGGL(kvd_pull_loop_kernel<T>, dim3(grid), dim3(T), 0, (hipStream_t)stream, p->geo, a);
+    } else {
+        const uint64_t gx = p->item_bound * (kChunkUnits / T);
+        if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
+        hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, (hipStream_t)stream,
+                           p->geo, a);
+    }
     KVD_HIP(hipGetLastError());
     return KVD_OK;
 }
@@ -846,17 +847,17 @@ int kvd_plan_stats(kvd_plan_t *p, void *stream, kvd_stats_t *out)
     if (!as_plan(p) || !out) return fail(KVD_ERR_INVALID, "null or wrong handle");
     memset(out, 0, sizeof(*out));
     out->num_requests = (uint32_t)p->reqs.size();
-    out->num_segments = (uint32_t)p->segs.size();
     out->relayout = p->geo.mode >= kRelayoutHT2TH ? 1u : 0u;
     out->num_src_blocks = p->used_src;
     out->num_dst_blocks = p->used_dst;
     out->num_transactions = p->txns_total;
     out->payload_bytes = p->payload_bytes;
-    if (!p->segs.empty()) {
+    if (!p->reqs.empty()) {
         KVD_HIP(hipStreamSynchronize((hipStream_t)stream));
-        std::vector<SegHeader> h(p->segs.size());
-        KVD_HIP(hipMemcpy(h.data(), p->segs_dev, h.size() * sizeof(SegHeader), hipMemcpyDeviceToHost));
-        for (const SegHeader &x : h) out->num_descriptors += x.n_desc;
+        Header h;
+        KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
+        out->num_descriptors = h.n_desc;
+        out->num_work_items = h.n_items;
     }
     return KVD_OK;
 }
@@ -866,34 +867,30 @@ int kvd_plan_get_descriptors(kvd_plan_t *p, void *stream, kvd_span_t *spans, kvd
 {
     if (!as_plan(p) || !n_out) return fail(KVD_ERR_INVALID, "null or wrong handle");
     *n_out = 0;
-    if (p->segs.empty()) return KVD_OK;
+    if (p->reqs.empty()) return KVD_OK;
     const bool relayout = p->geo.mode >= kRelayoutHT2TH;
     if ((relayout && !pieces) || (!relayout && !spans))
         return fail(KVD_ERR_INVALID, "output array for this plan's descriptor kind is null");
     KVD_HIP(hipStreamSynchronize((hipStream_t)stream));
-    std::vector<SegHeader> h(p->segs.size());
-    KVD_HIP(hipMemcpy(h.data(), p->segs_dev, h.size() * sizeof(SegHeader), hipMemcpyDeviceToHost));
-    std::vector<Desc> d(kSegCap);
-    uint64_t n = 0;
-    for (size_t s = 0; s < h.size(); ++s) {
-        if (h[s].n_desc > kSegCap) return fail(KVD_ERR_HIP, "corrupt segment header");
-        KVD_HIP(hipMemcpy(d.data(), p->desc_dev + s * kSegCap, h[s].n_desc * sizeof(Desc), hipMemcpyDeviceToHost));
-        for (uint32_t i = 0; i < h[s].n_desc; ++i, ++n) {
-            if (n >= cap) continue;
-            if (relayout) {
-                pieces[n].src_block = (int32_t)(d[i].src16 / p->geo.src_block16);
-                pieces[n].dst_block = (int32_t)(d[i].dst16 / p->geo.dst_block16);
-                pieces[n].src_token = d[i].a & 1023u;
-                pieces[n].dst_token = (d[i].a >> 10) & 1023u;
-                pieces[n].num_tokens = d[i].a >> 20;
-            } else {
-                spans[n].src_offset = (uint64_t)d[i].src16 * kUnitBytes;
-                spans[n].dst_offset = (uint64_t)d[i].dst16 * kUnitBytes;
-                spans[n].bytes = (uint64_t)(d[i].a - d[i].src16) * kUnitBytes;
-            }
+    Header h;
+    KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
+    if (h.n_desc > p->max_txns) return fail(KVD_ERR_HIP, "corrupt plan header");
+    std::vector<Desc> d(h.n_desc);
+    KVD_HIP(hipMemcpy(d.data(), p->desc_dev, (size_t)h.n_desc * sizeof(Desc), hipMemcpyDeviceToHost));
+    for (uint32_t i = 0; i < h.n_desc && i < cap; ++i) {
+        if (relayout) {
+            pieces[i].src_block = (int32_t)(d[i].src16 / p->geo.src_block16);
+            pieces[i].dst_block = (int32_t)(d[i].dst16 / p->geo.dst_block16);
+            pieces[i].src_token = d[i].a & 1023u;
+            pieces[i].dst_token = (d[i].a >> 10) & 1023u;
+            pieces[i].num_tokens = d[i].a >> 20;
+        } else {
+            spans[i].src_offset = (uint64_t)d[i].src16 * kUnitBytes;
+            spans[i].dst_offset = (uint64_t)d[i].dst16 * kUnitBytes;
+            spans[i].bytes = (uint64_t)(d[i].a - d[i].src16) * kUnitBytes;
         }
     }
-    *n_out = n;
+    *n_out = h.n_desc;
     return KVD_OK;
 }
 
@@ -903,14 +900,10 @@ int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream)
     if ((bytes % 16) || ((uintptr_t)dst % 16) || ((uintptr_t)src % 16))
         return fail(KVD_ERR_INVALID, "pointers and size must be multiples of 16 bytes");
     if (bytes == 0) return KVD_OK;
-    int dev = 0;
-    KVD_HIP(hipGetDevice(&dev));
-    int cus = 0;
-    KVD_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     const uint64_t units = bytes / 16;
-    const uint64_t want = (units + 1023) / 1024;
-    const uint32_t grid = (uint32_t)std::min<uint64_t>(want, (uint64_t)cus * 32);
-    hipLaunchKernelGGL(kvd_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst,
+    const uint64_t grid = (units + 255) / 256;
+    if (grid >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "copy too large for one launch");
+    hipLaunchKernelGGL(kvd_copy_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)stream, (u32x4 *)dst,
                        (const u32x4 *)src, units);
     KVD_HIP(hipGetLastError());
     return KVD_OK;

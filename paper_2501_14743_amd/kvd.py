@@ -21,6 +21,7 @@ KVD_ERR_INVALID, KVD_ERR_RANGE, KVD_ERR_MISMATCH = -1, -2, -3
 KVD_ERR_ALIAS, KVD_ERR_CAPACITY, KVD_ERR_HIP = -4, -5, -6
 KVD_LAYOUT_BHTD, KVD_LAYOUT_BTHD = 0, 1
 KVD_PLAN_NO_COALESCE = 1
+KVD_PLAN_PERSISTENT = 2
 LAYOUTS = {"BHTD": KVD_LAYOUT_BHTD, "BTHD": KVD_LAYOUT_BTHD}
 
 
@@ -54,11 +55,10 @@ class kvd_piece_t(ctypes.Structure):
 
 
 class kvd_stats_t(ctypes.Structure):
-    _fields_ = [("num_requests", ctypes.c_uint32), ("num_segments", ctypes.c_uint32),
-                ("relayout", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+    _fields_ = [("num_requests", ctypes.c_uint32), ("relayout", ctypes.c_uint32),
                 ("num_src_blocks", ctypes.c_uint64), ("num_dst_blocks", ctypes.c_uint64),
                 ("num_transactions", ctypes.c_uint64), ("num_descriptors", ctypes.c_uint64),
-                ("payload_bytes", ctypes.c_uint64)]
+                ("num_work_items", ctypes.c_uint64), ("payload_bytes", ctypes.c_uint64)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -153,7 +153,7 @@ def kvd_plan_reset(plan: int) -> None:
 def kvd_plan_stats(plan: int, stream: int = 0) -> dict:
     s = kvd_stats_t()
     _check(lib().kvd_plan_stats(plan, stream, ctypes.byref(s)))
-    return {k: int(getattr(s, k)) for k, _ in kvd_stats_t._fields_ if k != "reserved"}
+    return {k: int(getattr(s, k)) for k, _ in kvd_stats_t._fields_}
 
 
 def kvd_plan_get_descriptors(plan: int, stream: int = 0) -> np.ndarray:

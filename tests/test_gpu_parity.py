@@ -56,7 +56,7 @@ def test_descriptors_equal_oracle_coalescing(w):
     x.build()
     got = x.plan.descriptors(x.stream.cuda_stream)
     st = x.plan.stats(x.stream.cuda_stream)
-    assert st["num_segments"] == 1 and st["relayout"] == 0
+    assert st["relayout"] == 0
     want = tl.oracle_plan_descriptors(w, 0, 0)
     assert np.array_equal(got, want)
     assert st["num_descriptors"] == len(want) <= st["num_transactions"]
@@ -153,7 +153,8 @@ def test_layer_sub_range_and_mixed_ranges_in_one_plan():
         plan.build_descriptors(perm_s[a:b], perm_d[a:b], tokens, l0, l1, s.cuda_stream)
         w = wl.Workload("r", g, g, [wl.Request(tokens, perm_s[a:b], perm_d[a:b])], "bf16", 0, l0, l1)
         tl.oracle_pull_workload(w, src_host, want)
-    assert plan.stats(s.cuda_stream)["num_segments"] == 3  # a new group whenever the layer range changes
+    st = plan.stats(s.cuda_stream)
+    assert st["num_requests"] == 4 and st["num_transactions"] == (6 + 4) + (3 + 4) + (4 + 4) + 1
     plan.pull(s.cuda_stream)
     s.synchronize()
     G.assert_bytes_equal(dst.cpu().numpy(), want, "mixed layer ranges")
@@ -175,8 +176,31 @@ def test_merge_across_requests_as_in_queue_example():
     x.close()
 
 
-def test_many_transactions_span_several_descriptor_groups():
-    # 16-byte rows, one head: 10000 lone blocks -> more transactions than one LDS group holds
+def test_requests_with_different_layers_do_not_merge():
+    g = small_geom(num_layers=2)
+    src_host = wl.host_pool_values(g, "bf16", 4)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), 2, 8)
+    plan.build_descriptors([0], [5], 16, 0, 2)
+    plan.build_descriptors([1], [6], 16, 1, 2)   # continues the first on both sides, but other layers
+    plan.pull()
+    torch.cuda.synchronize()
+    assert plan.stats()["num_descriptors"] == 2
+    want = wl.host_pool_sentinel(g)
+    tl.oracle_pull_workload(wl.Workload("a", g, g, [wl.Request(16, np.array([0], np.int32), np.array([5], np.int32))], "bf16", 0), src_host, want)
+    tl.oracle_pull_workload(wl.Workload("b", g, g, [wl.Request(16, np.array([1], np.int32), np.array([6], np.int32))], "bf16", 0, 1, 2), src_host, want)
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "different layers")
+    plan.close()
+
+
+@pytest.mark.parametrize("w", [wl.config2(num_layers=2, pool_blocks=1024, tokens=3000),
+                               wl.config5(num_layers=2, src_pool_blocks=256, tokens=1500)], ids=lambda w: w.name)
+def test_persistent_grid_form_gives_the_same_bytes(w):
+    G.run_and_compare(w, host_src(w), flags=kvd.KVD_PLAN_PERSISTENT).close()
+
+
+def test_many_transactions_and_one_long_run():
+    # 16-byte rows, one head: 10000 lone blocks -> several passes of the coalescing workgroup
     g = wl.PoolGeometry(2, 20000, 16, 1, 8, 2, wl.BHTD)
     rng = np.random.default_rng(6)
     st = wl.scattered_table(rng, g.num_blocks, 10000)
@@ -184,13 +208,14 @@ def test_many_transactions_span_several_descriptor_groups():
     w = wl.Workload("groups", g, g, [wl.Request(10000 * 16 - 3, st, dt)], "bf16", 6)
     x = G.run_and_compare(w, host_src(w))
     st_ = x.plan.stats(x.stream.cuda_stream)
-    assert st_["num_segments"] == 3 and st_["num_descriptors"] == 10000
+    assert st_["num_descriptors"] == 10000 == st_["num_work_items"]
     x.close()
-    # the same with long contiguous runs: merging stops only at group boundaries
+    # the same as one long contiguous run: everything merges into a single descriptor
     ident = np.arange(10000, dtype=np.int32)
     w2 = wl.Workload("groups-contig", g, g, [wl.Request(10000 * 16, ident, ident + 5000)], "bf16", 6)
     x = G.run_and_compare(w2, host_src(w2))
-    assert x.plan.stats(x.stream.cuda_stream)["num_descriptors"] == 3
+    st_ = x.plan.stats(x.stream.cuda_stream)
+    assert st_["num_descriptors"] == 1 and st_["num_work_items"] == 10000 * 256 // 4096
     x.close()
 
 
