@@ -188,6 +188,10 @@ def main() -> int:
             kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr(), n, sh)
         torch.cuda.synchronize()
 
+    from paper_2501_14743_amd import traffic as traffic_record
+    rec = traffic_record.load_record(w.name)
+    traffic = rec["traffic_bytes_per_launch"] if rec else None
+
     out = {
         "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -202,7 +206,7 @@ def main() -> int:
         "us_per_request_batch": ms_per_step * 1e3,
         "pct_of_peak": 100.0 * achieved / PEAK_HBM_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBPS, "traffic": None,
+                     "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic,
                      "kernel": "kvd_pull_kernel", "kernel_us_mean": float(pull_ms.mean() * 1e3),
                      "kernel_us_min": float(pull_ms.min() * 1e3),
                      "algorithmic_bytes_per_launch": 2 * payload},

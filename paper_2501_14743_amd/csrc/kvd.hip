@@ -188,8 +188,8 @@ __device__ __forceinline__ uint32_t desc_items(const Geo &g, const Desc &d)
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildArgs a)
 {
-    __shared__ uint32_t s_end_s[kBuildThreads];
-    __shared__ uint32_t s_end_d[kBuildThreads];
+    __shared__ uint32_t s_buf[2 * kBuildThreads];
+    uint32_t *const s_end_s = s_buf, *const s_end_d = s_buf + kBuildThreads;
     __shared__ uint8_t s_brk[kBuildThreads];
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
 
@@ -299,17 +299,24 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     }
     const uint32_t n_items = carry;
 
-    // expand descriptors [from, n1) into work items [first_item, n_items); clear up to the bound
-    for (uint32_t c = first_item + tid; c < a.item_bound; c += kBuildThreads) {
-        Item it = {0, 0, 0, 0};
-        if (c < n_items) {
-            uint32_t lo = from, hi = n1;  // largest i with prefix[i] <= c
+    // expand descriptors [from, n1) into work items [first_item, n_items), a window of
+    // descriptors at a time with their prefixes staged in LDS for the item -> descriptor search
+    constexpr uint32_t kWin = 2 * kBuildThreads;
+    for (uint32_t w0 = from; w0 < n1; w0 += kWin) {
+        const uint32_t nw = min(kWin, n1 - w0);
+        for (uint32_t i = tid; i < nw; i += kBuildThreads) s_buf[i] = a.desc[w0 + i].prefix;
+        __syncthreads();
+        const uint32_t item_lo = s_buf[0];
+        const uint32_t item_hi = (w0 + nw == n1) ? n_items : a.desc[w0 + nw].prefix;
+        for (uint32_t c = item_lo + tid; c < item_hi; c += kBuildThreads) {
+            uint32_t lo = 0, hi = nw;  // largest i with prefix[i] <= c
             while (hi - lo > 1) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (a.desc[mid].prefix <= c) lo = mid; else hi = mid;
+                if (s_buf[mid] <= c) lo = mid; else hi = mid;
             }
-            const Desc d = a.desc[lo];
+            const Desc d = a.desc[w0 + lo];
             const uint32_t cl = c - d.prefix;
+            Item it;
             it.layers = a.layers;
             if (!relayout) {
                 it.src16 = d.src16 + cl * kChunkUnits;
@@ -326,9 +333,12 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
                 it.dst16 = d.dst16 + dt0 * d_tok;
                 it.n = row0 | ((rows - 1) << 20);
             }
+            a.items[c] = it;
         }
-        a.items[c] = it;
+        __syncthreads();
     }
+    // entries past the last work item up to the host's bound are marked unused
+    for (uint32_t c = n_items + tid; c < a.item_bound; c += kBuildThreads) a.items[c] = Item{0, 0, 0, 0};
     if (tid == 0) {
         a.hdr->n_desc = n1;
         a.hdr->n_items = n_items;
