@@ -94,9 +94,11 @@ def main() -> int:
     x = G.GpuTransfer(w, src, dst, stream=stream)
     sh = stream.cuda_stream
 
+    batch = len(w.requests) > 1  # several requests are appended with the one batched call
+
     def step(ev=None):
         x.plan.reset()
-        x.build()
+        x.build(batch)
         if ev is not None:
             ev[0].record(stream)
         x.plan.pull(sh)
@@ -143,12 +145,20 @@ def main() -> int:
         # build alone (host validation + one translate/coalesce kernel per request)
         def build_only():
             x.plan.reset()
-            x.build()
+            x.build(batch)
         t = time.perf_counter()
         for _ in range(20):
             build_only()
         torch.cuda.synchronize()
         extras["build_us"] = (time.perf_counter() - t) / 20 * 1e6
+        if batch:
+            t = time.perf_counter()
+            for _ in range(5):
+                x.plan.reset()
+                x.build(False)
+            torch.cuda.synchronize()
+            extras["build_one_call_per_request_us"] = (time.perf_counter() - t) / 5 * 1e6
+            build_only()
         # practical ceilings: one contiguous device-to-device copy of the payload
         n = min(payload, 1 << 30)
         a = torch.empty(n, dtype=torch.uint8, device="cuda")

@@ -169,6 +169,20 @@ int kvd_build_descriptors(kvd_plan_t *plan, const int32_t *src_block_table, uint
                           uint32_t layer_begin, uint32_t layer_end, void *stream);
 
 /*
+ * Append several requests that move the same layers with one call and one kernel launch per 512
+ * requests: the same queue, in array order, as n_requests calls of kvd_build_descriptors.
+ * src_block_tables[k] / dst_block_tables[k] (HOST arrays of n_src[k] / n_dst[k] ids) and
+ * seq_lens[k] describe request k; requests with seq_lens[k] == 0 are skipped.  All requests are
+ * validated before the plan is touched: on any error none of them is appended.
+ * Errors: as kvd_build_descriptors; the message names the offending request.
+ */
+int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
+                                const int32_t *const *src_block_tables, const uint32_t *n_src,
+                                const int32_t *const *dst_block_tables, const uint32_t *n_dst,
+                                const uint32_t *seq_lens, uint32_t layer_begin, uint32_t layer_end,
+                                void *stream);
+
+/*
  * Issue every queued (merged or unmerged) read of the plan at once, for all its requests,
  * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
  * blocking; section 4.3: all layers in a single shot).  Every read is cut into work items of at

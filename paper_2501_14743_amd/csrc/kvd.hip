@@ -2,7 +2,7 @@
 //
 // Data path of KVDirect (arXiv 2501.14743), sections 4.1-4.3, with both pools in one GPU's
 // HBM.  Kernels:
-//   kvd_build_kernel   one workgroup per appended request: block ids -> byte ranges (section
+//   kvd_build_kernel   one workgroup per appended request or batch: block ids -> byte ranges (section
 //                      4.1), coalescing of queued ranges with a wave64 ballot + prefix scan
 //                      (section 4.2), then expansion of the coalesced ranges into a table of
 //                      fixed 4 KiB work items.
@@ -106,15 +106,25 @@ struct Geo {
 
 // ------------------------------------------------------------------ build: translate + coalesce + expand
 
+constexpr uint32_t kMaxBatch = 512;  // requests one launch of the build kernel can take
+
+// One request of a batch, as the build kernel sees it.
+struct ReqDev {
+    uint32_t table_off_src, table_off_dst;  // where its block tables start in the plan's tables
+    uint32_t seq_len;
+    uint32_t txn_begin;                     // its first read transaction within the batch
+};
+
 struct BuildArgs {
-    const int32_t *src_table;  // this request's tables (device-visible pinned host memory)
-    const int32_t *dst_table;
+    const int32_t *tables_src;  // the plan's block tables (device-visible pinned host memory)
+    const int32_t *tables_dst;
+    const ReqDev *reqs;         // the batch (device-visible pinned host memory)
+    ReqDev first;               // copy of reqs[0]: a single request needs no extra host read
     Desc *desc;
     Item *items;
     Header *hdr;
-    uint32_t seq_len;
-    uint32_t n_txn;            // read transactions of this request per (layer, K/V)
-    uint32_t n_single;         // head-major, equal block size: leading whole-block transactions
+    uint32_t n_req;
+    uint32_t n_txn;            // read transactions of the whole batch per (layer, K/V)
     uint32_t layers;           // layer_begin | num_layers << 16
     uint32_t fresh;            // 1: the plan is empty (header contents are stale)
     uint32_t may_merge_prev;   // 1: the previous request moves the same layers
@@ -125,19 +135,20 @@ struct Txn {
     uint32_t s16, d16, len16, meta;
 };
 
-// Section 4.1: block id -> offset through the strides.  Transaction j of a request, in the
+// Section 4.1: block id -> offset through the strides.  Transaction j of request rq, in the
 // order Transfer() is called for its blocks.
-__device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, uint32_t j)
+__device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, const ReqDev rq, uint32_t j)
 {
     uint32_t piece, head = 0;
     bool per_head = false;
     if (g.mode == kSpanHeadMajor) {
         if (g.tb_src == g.tb_dst) {
-            if (j < a.n_single) {
+            const uint32_t n_single = fdiv(rq.seq_len, g.div_tb_src);  // leading whole blocks
+            if (j < n_single) {
                 piece = j;
             } else {
-                piece = a.n_single;
-                head = j - a.n_single;
+                piece = n_single;
+                head = j - n_single;
                 per_head = true;
             }
         } else {
@@ -149,11 +160,11 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, uint32
         piece = j;
     }
     const uint32_t t0 = piece * g.piece_tokens;
-    const uint32_t ntok = min(g.piece_tokens, a.seq_len - t0);
+    const uint32_t ntok = min(g.piece_tokens, rq.seq_len - t0);
     const uint32_t sb_i = fdiv(t0, g.div_tb_src), db_i = fdiv(t0, g.div_tb_dst);
     const uint32_t st0 = t0 - sb_i * g.tb_src, dt0 = t0 - db_i * g.tb_dst;
-    const uint32_t sbase = (uint32_t)a.src_table[sb_i] * g.src_block16;
-    const uint32_t dbase = (uint32_t)a.dst_table[db_i] * g.dst_block16;
+    const uint32_t sbase = (uint32_t)a.tables_src[rq.table_off_src + sb_i] * g.src_block16;
+    const uint32_t dbase = (uint32_t)a.tables_dst[rq.table_off_dst + db_i] * g.dst_block16;
     Txn t;
     t.meta = 0;
     if (g.mode == kSpanTokenMajor) {
@@ -191,8 +202,13 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     uint32_t *const s_end_s = s_buf, *const s_end_d = s_buf + kBuildThreads;
     __shared__ uint8_t s_brk[kBuildThreads];
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
+    __shared__ ReqDev s_req[kMaxBatch];
 
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    if (a.n_req > 1) {
+        for (uint32_t i = tid; i < a.n_req; i += kBuildThreads) s_req[i] = a.reqs[i];
+        __syncthreads();
+    }
     const bool relayout = g.mode >= kRelayoutHT2TH;
     const bool never_merge = relayout || a.no_coalesce;
     const uint32_t n0 = a.fresh ? 0u : a.hdr->n_desc;
@@ -214,7 +230,18 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         const uint32_t j = tile + tid;
         const bool valid = j < a.n_txn;
         Txn t = {0, 0, 0, 0};
-        if (valid) t = make_txn(g, a, j);
+        if (valid) {
+            ReqDev rq = a.first;
+            if (a.n_req > 1) {
+                uint32_t lo = 0, hi = a.n_req;  // the request transaction j belongs to
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (s_req[mid].txn_begin <= j) lo = mid; else hi = mid;
+                }
+                rq = s_req[lo];
+            }
+            t = make_txn(g, a, rq, j - rq.txn_begin);
+        }
         s_end_s[tid] = t.s16 + t.len16;
         s_end_d[tid] = t.d16 + t.len16;
         __syncthreads();
@@ -496,6 +523,7 @@ struct kvd_plan {
     int num_cus;
     int32_t *tables_src, *tables_dst;  // pinned host, device-visible
     int32_t *tables_src_dev, *tables_dst_dev;
+    ReqDev *reqs_pinned, *reqs_pinned_dev;  // one entry per request, same kind of memory
     Desc *desc_dev;
     Item *items_dev;
     Header *hdr_dev;
@@ -578,6 +606,8 @@ int ensure_allocated(kvd_plan *p)
     KVD_HIP(hipHostMalloc((void **)&p->tables_dst, tb, hipHostMallocMapped));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->tables_src_dev, p->tables_src, 0));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->tables_dst_dev, p->tables_dst, 0));
+    KVD_HIP(hipHostMalloc((void **)&p->reqs_pinned, (size_t)p->max_requests * sizeof(ReqDev), hipHostMallocMapped));
+    KVD_HIP(hipHostGetDevicePointer((void **)&p->reqs_pinned_dev, p->reqs_pinned, 0));
     KVD_HIP(hipMalloc((void **)&p->desc_dev, (size_t)p->max_txns * sizeof(Desc)));
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
@@ -592,6 +622,7 @@ void release_plan(kvd_plan *p)
         if (p->build_pending) (void)hipEventSynchronize(p->build_done);
         (void)hipHostFree(p->tables_src);
         (void)hipHostFree(p->tables_dst);
+        (void)hipHostFree(p->reqs_pinned);
         (void)hipFree(p->desc_dev);
         (void)hipFree(p->items_dev);
         (void)hipFree(p->hdr_dev);
@@ -719,103 +750,150 @@ int kvd_plan_reset(kvd_plan_t *p)
     return KVD_OK;
 }
 
-int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
-                          const int32_t *dst_tbl, uint32_t n_dst, uint32_t seq_len,
-                          uint32_t layer_begin, uint32_t layer_end, void *stream)
+int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_t *const *src_tbls,
+                                const uint32_t *n_src, const int32_t *const *dst_tbls, const uint32_t *n_dst,
+                                const uint32_t *seq_lens, uint32_t layer_begin, uint32_t layer_end, void *stream)
 {
     if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
     if (layer_begin >= layer_end) return fail(KVD_ERR_INVALID, "empty layer range [%u, %u)", layer_begin, layer_end);
     if (layer_end > p->src.num_layers || layer_end > p->dst.num_layers)
         return fail(KVD_ERR_RANGE, "layer range [%u, %u) outside a pool", layer_begin, layer_end);
-    if (seq_len == 0) return KVD_OK;
-    if (!src_tbl || !dst_tbl) return fail(KVD_ERR_INVALID, "null block table");
+    if (n_requests == 0) return KVD_OK;
+    if (!src_tbls || !dst_tbls || !n_src || !n_dst || !seq_lens) return fail(KVD_ERR_INVALID, "null argument");
     const Geo &g = p->geo;
-    const uint32_t need_src = ceil_div(seq_len, g.tb_src), need_dst = ceil_div(seq_len, g.tb_dst);
-    if (n_src < need_src || n_dst < need_dst)
-        return fail(KVD_ERR_RANGE, "block table too short for %u tokens (source %u of %u, destination %u of %u)",
-                    seq_len, n_src, need_src, n_dst, need_dst);
-    for (uint32_t i = 0; i < need_src; ++i)
-        if (src_tbl[i] < 0 || (uint32_t)src_tbl[i] >= p->src.num_blocks)
-            return fail(KVD_ERR_RANGE, "source block id %d at entry %u outside [0, %u)", src_tbl[i], i, p->src.num_blocks);
-    for (uint32_t i = 0; i < need_dst; ++i)
-        if (dst_tbl[i] < 0 || (uint32_t)dst_tbl[i] >= p->dst.num_blocks)
-            return fail(KVD_ERR_RANGE, "destination block id %d at entry %u outside [0, %u)", dst_tbl[i], i, p->dst.num_blocks);
-    // every destination byte is written at most once per plan: 2 marks this request's blocks
-    // until the call is sure to succeed, 1 marks blocks of accepted requests
-    auto unmark = [&](uint32_t upto) {
-        for (uint32_t k = 0; k < upto; ++k)
-            if (p->dst_used[(uint32_t)dst_tbl[k]] == 2) p->dst_used[(uint32_t)dst_tbl[k]] = 0;
-    };
-    for (uint32_t i = 0; i < need_dst; ++i) {
-        uint8_t &u = p->dst_used[(uint32_t)dst_tbl[i]];
-        if (u) {
-            unmark(i);
-            return fail(KVD_ERR_ALIAS, "destination block %d (entry %u) is already a target in this plan", dst_tbl[i], i);
-        }
-        u = 2;
+
+    // 1. everything that can be checked without touching the plan
+    uint64_t add_src = 0, add_dst = 0, add_txn = 0, add_items = 0, add_reqs = 0;
+    for (uint32_t k = 0; k < n_requests; ++k) {
+        const uint32_t seq_len = seq_lens[k];
+        if (seq_len == 0) continue;
+        const int32_t *st = src_tbls[k], *dt = dst_tbls[k];
+        if (!st || !dt) return fail(KVD_ERR_INVALID, "request %u: null block table", k);
+        const uint32_t need_src = ceil_div(seq_len, g.tb_src), need_dst = ceil_div(seq_len, g.tb_dst);
+        if (n_src[k] < need_src || n_dst[k] < need_dst)
+            return fail(KVD_ERR_RANGE, "request %u: block table too short for %u tokens (source %u of %u, destination %u of %u)",
+                        k, seq_len, n_src[k], need_src, n_dst[k], need_dst);
+        for (uint32_t i = 0; i < need_src; ++i)
+            if (st[i] < 0 || (uint32_t)st[i] >= p->src.num_blocks)
+                return fail(KVD_ERR_RANGE, "request %u: source block id %d at entry %u outside [0, %u)", k, st[i], i, p->src.num_blocks);
+        for (uint32_t i = 0; i < need_dst; ++i)
+            if (dt[i] < 0 || (uint32_t)dt[i] >= p->dst.num_blocks)
+                return fail(KVD_ERR_RANGE, "request %u: destination block id %d at entry %u outside [0, %u)", k, dt[i], i, p->dst.num_blocks);
+        uint32_t n_txn = 0, n_single = 0, items = 0;
+        request_sizes(g, seq_len, &n_txn, &n_single, &items);
+        add_src += need_src;
+        add_dst += need_dst;
+        add_txn += n_txn;
+        add_items += items;
+        ++add_reqs;
     }
-    uint32_t n_txn = 0, n_single = 0, items = 0;
-    request_sizes(g, seq_len, &n_txn, &n_single, &items);
-    if (p->reqs.size() >= p->max_requests) {
-        unmark(need_dst);
-        return fail(KVD_ERR_CAPACITY, "plan already holds %u requests", p->max_requests);
-    }
-    if (p->used_src + need_src > p->max_total_blocks || p->used_dst + need_dst > p->max_total_blocks ||
-        p->txns_total + n_txn > p->max_txns || p->item_bound + items > p->max_items) {
-        unmark(need_dst);
+    if (add_reqs == 0) return KVD_OK;
+    if (p->reqs.size() + add_reqs > p->max_requests)
+        return fail(KVD_ERR_CAPACITY, "plan holds at most %u requests", p->max_requests);
+    if (p->used_src + add_src > p->max_total_blocks || p->used_dst + add_dst > p->max_total_blocks ||
+        p->txns_total + add_txn > p->max_txns || p->item_bound + add_items > p->max_items)
         return fail(KVD_ERR_CAPACITY, "plan holds at most %u block-table entries per side", p->max_total_blocks);
+
+    // 2. every destination byte is written at most once per plan: 2 marks this call's blocks
+    //    until the call is sure to succeed, 1 marks blocks of accepted requests
+    auto unmark_call = [&](uint32_t upto_req, uint32_t upto_entry) {
+        for (uint32_t k = 0; k <= upto_req && k < n_requests; ++k) {
+            if (seq_lens[k] == 0) continue;
+            const uint32_t need = (k == upto_req) ? upto_entry : ceil_div(seq_lens[k], g.tb_dst);
+            for (uint32_t i = 0; i < need; ++i)
+                if (p->dst_used[(uint32_t)dst_tbls[k][i]] == 2) p->dst_used[(uint32_t)dst_tbls[k][i]] = 0;
+        }
+    };
+    for (uint32_t k = 0; k < n_requests; ++k) {
+        if (seq_lens[k] == 0) continue;
+        const uint32_t need_dst = ceil_div(seq_lens[k], g.tb_dst);
+        for (uint32_t i = 0; i < need_dst; ++i) {
+            uint8_t &u = p->dst_used[(uint32_t)dst_tbls[k][i]];
+            if (u) {
+                unmark_call(k, i);
+                return fail(KVD_ERR_ALIAS, "request %u: destination block %d (entry %u) is already a target in this plan",
+                            k, dst_tbls[k][i], i);
+            }
+            u = 2;
+        }
     }
     int rc = ensure_allocated(p);
     if (rc != KVD_OK) {
-        unmark(need_dst);
+        unmark_call(n_requests, 0);
         return rc;
     }
-    for (uint32_t i = 0; i < need_dst; ++i) p->dst_used[(uint32_t)dst_tbl[i]] = 1;
 
-    ReqHost r;
-    r.table_off_src = (uint32_t)p->used_src;
-    r.table_off_dst = (uint32_t)p->used_dst;
-    r.n_src = need_src;
-    r.n_dst = need_dst;
-    r.seq_len = seq_len;
-    r.layer_begin = layer_begin;
-    r.layer_end = layer_end;
-    memcpy(p->tables_src + r.table_off_src, src_tbl, (size_t)need_src * sizeof(int32_t));
-    memcpy(p->tables_dst + r.table_off_dst, dst_tbl, (size_t)need_dst * sizeof(int32_t));
-    const bool fresh = p->reqs.empty();
-    const bool same_layers = !fresh && p->reqs.back().layer_begin == layer_begin &&
+    // 3. commit on the host, then one launch per kMaxBatch requests
+    const size_t first_new = p->reqs.size();
+    const bool same_layers = first_new > 0 && p->reqs.back().layer_begin == layer_begin &&
                              p->reqs.back().layer_end == layer_end;
-
-    BuildArgs a;
-    a.src_table = p->tables_src_dev + r.table_off_src;
-    a.dst_table = p->tables_dst_dev + r.table_off_dst;
-    a.desc = p->desc_dev;
-    a.items = p->items_dev;
-    a.hdr = p->hdr_dev;
-    a.seq_len = seq_len;
-    a.n_txn = n_txn;
-    a.n_single = n_single;
-    a.layers = layer_begin | ((layer_end - layer_begin) << 16);
-    a.fresh = fresh ? 1u : 0u;
-    a.may_merge_prev = same_layers ? 1u : 0u;
-    a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
-    hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
-    hipError_t launch = hipGetLastError();
-    if (launch == hipSuccess) launch = hipEventRecord(p->build_done, (hipStream_t)stream);
-    if (launch != hipSuccess) {
-        for (uint32_t i = 0; i < need_dst; ++i) p->dst_used[(uint32_t)dst_tbl[i]] = 0;
-        return fail(KVD_ERR_HIP, "launch of the build kernel failed: %s", hipGetErrorString(launch));
+    for (uint32_t k = 0; k < n_requests; ++k) {
+        const uint32_t seq_len = seq_lens[k];
+        if (seq_len == 0) continue;
+        ReqHost r;
+        r.table_off_src = (uint32_t)p->used_src;
+        r.table_off_dst = (uint32_t)p->used_dst;
+        r.n_src = ceil_div(seq_len, g.tb_src);
+        r.n_dst = ceil_div(seq_len, g.tb_dst);
+        r.seq_len = seq_len;
+        r.layer_begin = layer_begin;
+        r.layer_end = layer_end;
+        memcpy(p->tables_src + r.table_off_src, src_tbls[k], (size_t)r.n_src * sizeof(int32_t));
+        memcpy(p->tables_dst + r.table_off_dst, dst_tbls[k], (size_t)r.n_dst * sizeof(int32_t));
+        for (uint32_t i = 0; i < r.n_dst; ++i) p->dst_used[(uint32_t)dst_tbls[k][i]] = 1;
+        p->used_src += r.n_src;
+        p->used_dst += r.n_dst;
+        p->payload_bytes += (uint64_t)seq_len * (layer_end - layer_begin) * 2 * g.hk * g.du * kUnitBytes;
+        p->reqs.push_back(r);
     }
-    p->build_pending = true;
-
-    p->used_src += need_src;
-    p->used_dst += need_dst;
-    p->txns_total += n_txn;
-    p->item_bound += items;
     p->max_layers = std::max(p->max_layers, layer_end - layer_begin);
-    p->payload_bytes += (uint64_t)seq_len * (layer_end - layer_begin) * 2 * g.hk * g.du * kUnitBytes;
-    p->reqs.push_back(r);
+    for (size_t b0 = first_new; b0 < p->reqs.size(); b0 += kMaxBatch) {
+        const uint32_t nb = (uint32_t)std::min<size_t>(kMaxBatch, p->reqs.size() - b0);
+        uint32_t batch_txn = 0, batch_items = 0;
+        for (uint32_t i = 0; i < nb; ++i) {
+            const ReqHost &r = p->reqs[b0 + i];
+            uint32_t n_txn = 0, n_single = 0, items = 0;
+            request_sizes(g, r.seq_len, &n_txn, &n_single, &items);
+            p->reqs_pinned[b0 + i] = ReqDev{r.table_off_src, r.table_off_dst, r.seq_len, batch_txn};
+            batch_txn += n_txn;
+            batch_items += items;
+        }
+        BuildArgs a;
+        a.tables_src = p->tables_src_dev;
+        a.tables_dst = p->tables_dst_dev;
+        a.reqs = p->reqs_pinned_dev + b0;
+        a.first = p->reqs_pinned[b0];
+        a.desc = p->desc_dev;
+        a.items = p->items_dev;
+        a.hdr = p->hdr_dev;
+        a.n_req = nb;
+        a.n_txn = batch_txn;
+        a.layers = layer_begin | ((layer_end - layer_begin) << 16);
+        a.fresh = (b0 == 0) ? 1u : 0u;
+        a.may_merge_prev = (b0 > first_new || same_layers) ? 1u : 0u;
+        a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
+        hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
+        hipError_t launch = hipGetLastError();
+        if (launch == hipSuccess) launch = hipEventRecord(p->build_done, (hipStream_t)stream);
+        if (launch != hipSuccess) {
+            // the plan's device state no longer matches the host's: drop everything queued
+            p->build_pending = true;
+            (void)kvd_plan_reset(p);
+            return fail(KVD_ERR_HIP, "launch of the build kernel failed (plan was reset): %s", hipGetErrorString(launch));
+        }
+        p->build_pending = true;
+        p->txns_total += batch_txn;
+        p->item_bound += batch_items;
+    }
     return KVD_OK;
+}
+
+int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
+                          const int32_t *dst_tbl, uint32_t n_dst, uint32_t seq_len,
+                          uint32_t layer_begin, uint32_t layer_end, void *stream)
+{
+    return kvd_build_descriptors_batch(p, 1, &src_tbl, &n_src, &dst_tbl, &n_dst, &seq_len, layer_begin,
+                                       layer_end, stream);
 }
 
 int kvd_pull(kvd_plan_t *p, void *stream)

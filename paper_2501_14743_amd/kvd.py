@@ -79,6 +79,9 @@ def lib() -> ctypes.CDLL:
     L.kvd_pool_create.argtypes = [ctypes.POINTER(kvd_pool_desc_t), ctypes.POINTER(vp)]
     L.kvd_plan_create.argtypes = [vp, vp, u32, u32, u32, ctypes.POINTER(vp)]
     L.kvd_build_descriptors.argtypes = [vp, i32p, u32, i32p, u32, u32, u32, u32, vp]
+    L.kvd_build_descriptors_batch.argtypes = [vp, u32, ctypes.POINTER(i32p), ctypes.POINTER(u32),
+                                              ctypes.POINTER(i32p), ctypes.POINTER(u32), ctypes.POINTER(u32),
+                                              u32, u32, vp]
     L.kvd_pull.argtypes = [vp, vp]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
     L.kvd_plan_reset.argtypes = [vp]
@@ -88,7 +91,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_copy_plain.argtypes = [vp, vp, u64, vp]
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
-    for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_pull",
+    for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
                  "kvd_pull_blockwise_memcpy", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain"):
         getattr(L, name).restype = ctypes.c_int
@@ -136,6 +139,20 @@ def kvd_build_descriptors(plan: int, src_block_table, dst_block_table, seq_len: 
     st, dt = _table(src_block_table), _table(dst_block_table)
     _check(lib().kvd_build_descriptors(plan, _i32p(st), st.size, _i32p(dt), dt.size, seq_len,
                                        layer_begin, layer_end, stream))
+
+
+def kvd_build_descriptors_batch(plan: int, src_block_tables: Sequence, dst_block_tables: Sequence,
+                                seq_lens: Sequence[int], layer_begin: int, layer_end: int, stream: int = 0) -> None:
+    n = len(seq_lens)
+    assert len(src_block_tables) == n and len(dst_block_tables) == n
+    sts, dts = [_table(t) for t in src_block_tables], [_table(t) for t in dst_block_tables]
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    sp = (i32p * n)(*[_i32p(t) if t.size else i32p() for t in sts])
+    dp = (i32p * n)(*[_i32p(t) if t.size else i32p() for t in dts])
+    ns = (ctypes.c_uint32 * n)(*[t.size for t in sts])
+    nd = (ctypes.c_uint32 * n)(*[t.size for t in dts])
+    sl = (ctypes.c_uint32 * n)(*[int(x) for x in seq_lens])
+    _check(lib().kvd_build_descriptors_batch(plan, n, sp, ns, dp, nd, sl, layer_begin, layer_end, stream))
 
 
 def kvd_pull(plan: int, stream: int = 0) -> None:
@@ -215,6 +232,9 @@ class Plan:
 
     def build_descriptors(self, src_table, dst_table, seq_len, layer_begin, layer_end, stream=0):
         kvd_build_descriptors(self.handle, src_table, dst_table, seq_len, layer_begin, layer_end, stream)
+
+    def build_descriptors_batch(self, src_tables, dst_tables, seq_lens, layer_begin, layer_end, stream=0):
+        kvd_build_descriptors_batch(self.handle, src_tables, dst_tables, seq_lens, layer_begin, layer_end, stream)
 
     def pull(self, stream=0):
         kvd_pull(self.handle, stream)

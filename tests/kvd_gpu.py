@@ -47,16 +47,23 @@ class GpuTransfer:
         max_blocks = sum(max(len(r.src_table), len(r.dst_table)) for r in w.requests) + 1
         self.plan = kvd.Plan(self.src_pool, self.dst_pool, max(1, len(w.requests)), max_blocks, flags)
 
-    def build(self):
-        for r in self.w.requests:
-            self.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, self.w.layer_begin,
-                                        self.w.layer_end, self.stream.cuda_stream)
+    def build(self, batch: bool = False):
+        """Append every request of the workload: one call each, or one batched call."""
+        w = self.w
+        if batch:
+            self.plan.build_descriptors_batch([r.src_table for r in w.requests], [r.dst_table for r in w.requests],
+                                              [r.seq_len for r in w.requests], w.layer_begin, w.layer_end,
+                                              self.stream.cuda_stream)
+            return
+        for r in w.requests:
+            self.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, w.layer_begin, w.layer_end,
+                                        self.stream.cuda_stream)
 
     def pull(self):
         self.plan.pull(self.stream.cuda_stream)
 
-    def run(self):
-        self.build()
+    def run(self, batch: bool = False):
+        self.build(batch)
         self.pull()
         self.stream.synchronize()
         return self

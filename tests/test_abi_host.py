@@ -114,6 +114,30 @@ def test_build_descriptors_validates_before_launching():
         kvd.kvd_pull(0)
 
 
+def test_batch_is_all_or_nothing():
+    g = geom()
+    plan = kvd.Plan(kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g), 4, 32)
+    a, b = np.arange(0, 4, dtype=np.int32), np.arange(4, 8, dtype=np.int32)
+    # second request reuses a destination block of the first: nothing is appended, marks are undone
+    msg = expect(kvd.KVD_ERR_ALIAS, plan.build_descriptors_batch, [a, b], [a, np.array([4, 5, 2, 7], np.int32)],
+                 [64, 64], 0, 2)
+    assert "request 1" in msg
+    msg = expect(kvd.KVD_ERR_RANGE, plan.build_descriptors_batch, [a, b], [a, np.array([4, 5, 64, 7], np.int32)],
+                 [64, 64], 0, 2)
+    assert "request 1" in msg
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors_batch, [a, b[:3]], [a, b], [64, 64], 0, 2)
+    expect(kvd.KVD_ERR_CAPACITY, plan.build_descriptors_batch, [a] * 5, [a, b, a + 8, a + 12, a + 16], [64] * 5, 0, 2)
+    assert plan.stats()["num_requests"] == 0
+    # zero-length requests are skipped, an all-empty batch succeeds without a GPU
+    plan.build_descriptors_batch([a, b], [a, b], [0, 0], 0, 2)
+    plan.build_descriptors_batch([], [], [], 0, 2)
+    import torch
+    if not torch.cuda.is_available():
+        # a valid batch gets as far as the GPU allocation and leaves no marks behind
+        expect(kvd.KVD_ERR_HIP, plan.build_descriptors_batch, [a, b], [a, b], [64, 64], 0, 2)
+        expect(kvd.KVD_ERR_HIP, plan.build_descriptors_batch, [a, b], [a, b], [64, 64], 0, 2)
+
+
 def test_valid_build_needs_a_gpu_and_says_so():
     import torch
     if torch.cuda.is_available():

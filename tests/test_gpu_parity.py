@@ -68,6 +68,50 @@ def test_descriptors_equal_oracle_coalescing(w):
     x.close()
 
 
+def test_batched_build_equals_one_call_per_request():
+    w = wl.config3(num_layers=2, num_requests=40, median=200.0, hi=3000)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    one = G.GpuTransfer(w, src, dst)
+    one.build(batch=False)
+    d_one = one.plan.descriptors(one.stream.cuda_stream)
+    st_one = one.plan.stats(one.stream.cuda_stream)
+    one.close()
+    x = G.GpuTransfer(w, src, dst)
+    x.run(batch=True)
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), d_one)
+    assert x.plan.stats(x.stream.cuda_stream) == st_one
+    assert np.array_equal(d_one, tl.oracle_plan_descriptors(w, 0, 0))
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "batched build")
+    x.close()
+
+
+def test_batch_larger_than_one_launch_takes():
+    # 700 short requests: more than one build launch holds; mixed with an earlier single request
+    g = wl.PoolGeometry(1, 4096, 16, 2, 64, 2, wl.BHTD)
+    rng = np.random.default_rng(12)
+    free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+    reqs = []
+    for _ in range(701):
+        t = int(rng.integers(1, 70))
+        n = wl.blocks_for(t, 16)
+        reqs.append(wl.Request(t, wl.fragmented_allocation(rng, free_s, n, 4), wl.fragmented_allocation(rng, free_d, n, 4)))
+    w = wl.Workload("many", g, g, reqs, "bf16", 12)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst)
+    r0 = reqs[0]
+    x.plan.build_descriptors(r0.src_table, r0.dst_table, r0.seq_len, 0, 1, x.stream.cuda_stream)
+    x.plan.build_descriptors_batch([r.src_table for r in reqs[1:]], [r.dst_table for r in reqs[1:]],
+                                   [r.seq_len for r in reqs[1:]], 0, 1, x.stream.cuda_stream)
+    x.pull()
+    x.stream.synchronize()
+    assert x.plan.stats(x.stream.cuda_stream)["num_requests"] == 701
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), tl.oracle_plan_descriptors(w, 0, 0))
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "701 requests")
+    x.close()
+
+
 def test_no_coalesce_flag_keeps_every_transaction_and_same_bytes():
     w = wl.config2(num_layers=2, pool_blocks=1024, tokens=3000)
     x = G.run_and_compare(w, host_src(w), flags=kvd.KVD_PLAN_NO_COALESCE)
@@ -318,7 +362,7 @@ def _check_full(w, sample_layers):
     checksum = [int(src.view(torch.int16)[i::9973][:4096].sum()) for i in range(3)]
     x = G.GpuTransfer(w, src, dst)
     say(f"{w.name}: build + pull")
-    x.run()
+    x.run(batch=len(w.requests) > 1)  # the launch configuration bench.py times
     st = x.plan.stats(x.stream.cuda_stream)
     say(f"{w.name}: {st}")
     moved16 = st["payload_bytes"] // 2
