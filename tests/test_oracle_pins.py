@@ -73,6 +73,25 @@ def test_block8_is_two_transactions_and_blocks01_merge():
     assert m.tolist() == [[0, 0, int(GOLD["blocks01_merged_bytes"])]]
 
 
+def test_partial_last_block_moves_only_the_request_tokens():
+    """Tokens beyond seq_len never appear in a transaction (closed forms for both inner orders)."""
+    t = paper_tensor()  # [token][head][dim] inside a block: a token range is one byte range
+    q = orc.request_transactions(t, t, 0, [3, 7], [2, 9], 16 + 5)
+    assert q.tolist() == [[3 * 8192, 2 * 8192, 8192], [7 * 8192, 9 * 8192, 5 * 2 * 128 * 2]]
+    assert q[:, 2].sum() == orc.transfer_bytes(21, 1, 2, 128, 2) // 2
+    # [head][token][dim]: the 5 tokens are 5*128 elements in each of the two head planes
+    hm = orc.Tensor(None, 0, [orc.B, orc.KV, orc.H, orc.L, orc.D], [10, 2, 2, 16, 128],
+                    [4096, 40960, 2048, 128, 1], 2)
+    q = orc.request_transactions(hm, hm, 1, [3, 7], [2, 9], 16 + 5)
+    v = 40960 * 2
+    assert q.tolist() == [[v + 3 * 8192, v + 2 * 8192, 8192],
+                          [v + 7 * 8192, v + 9 * 8192, 5 * 128 * 2],
+                          [v + 7 * 8192 + 4096, v + 9 * 8192 + 4096, 5 * 128 * 2]]
+    # a single token, and an exact multiple (no tail at all)
+    assert orc.request_transactions(t, t, 0, [4], [5], 1).tolist() == [[4 * 8192, 5 * 8192, 512]]
+    assert len(orc.request_transactions(hm, hm, 0, [1, 2], [3, 4], 32)) == 2
+
+
 # ---------------------------------------------------------------- section 4.2 queue example
 
 def test_queue_example_merges_across_requests():
