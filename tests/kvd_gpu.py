@@ -50,6 +50,8 @@ class GpuTransfer:
     def build(self, batch: bool = False):
         """Append every request of the workload: one call each, or one batched call."""
         w = self.w
+        # pools are filled by torch on its current stream; order this stream after that work
+        self.stream.wait_stream(torch.cuda.current_stream())
         if batch:
             self.plan.build_descriptors_batch([r.src_table for r in w.requests], [r.dst_table for r in w.requests],
                                               [r.seq_len for r in w.requests], w.layer_begin, w.layer_end,

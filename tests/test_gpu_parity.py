@@ -191,6 +191,7 @@ def test_layer_sub_range_and_mixed_ranges_in_one_plan():
     sp, dp = kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g)
     plan = kvd.Plan(sp, dp, 4, 96)
     s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())  # the pools were filled on torch's stream
     reqs = [(100, 0, 10, 1, 3), (50, 10, 14, 1, 3), (77, 14, 19, 0, 4), (16, 19, 20, 3, 4)]
     want = wl.host_pool_sentinel(g)
     for tokens, a, b, l0, l1 in reqs:
@@ -351,6 +352,55 @@ def test_plain_copy():
     assert torch.equal(a, b)
     with pytest.raises(kvd.KvdError):
         kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr() + 1, 16)
+
+
+@pytest.mark.parametrize("gs,gd", [
+    (wl.PoolGeometry(2, 6, 1024, 2, 8, 2, wl.BHTD), wl.PoolGeometry(2, 24, 256, 2, 8, 2, wl.BTHD)),
+    (wl.PoolGeometry(2, 6, 1024, 3, 8, 2, wl.BTHD), wl.PoolGeometry(2, 6, 1024, 3, 8, 2, wl.BHTD)),
+    (wl.PoolGeometry(2, 6, 1024, 2, 8, 2, wl.BHTD), wl.PoolGeometry(2, 6, 1024, 2, 8, 2, wl.BHTD)),
+], ids=["1024-to-256-relayout", "1024-relayout-back", "1024-same"])
+def test_largest_block_size(gs, gd):
+    w = one_request(gs, gd, 5000)
+    G.run_and_compare(w, host_src(w)).close()
+
+
+def test_slab_larger_than_4_gib():
+    """Block offsets beyond 2^32 bytes inside one (layer, K/V) slab; checked through a compact
+    renumbering of the blocks that are used (the oracle never sees the 10 GiB pools)."""
+    nb = 163840  # x 32 KiB = 5 GiB per slab
+    g = wl.PoolGeometry(1, nb, 16, 8, 128, 2, wl.BHTD)
+    rng = np.random.default_rng(21)
+    n = 300
+    st = np.concatenate([rng.choice(np.arange(nb - 5000, nb), n - 20, replace=False), rng.choice(5000, 20, replace=False)])
+    dt = np.concatenate([rng.choice(np.arange(nb - 5000, nb), n - 20, replace=False), rng.choice(5000, 20, replace=False)])
+    st, dt = rng.permutation(st).astype(np.int32), rng.permutation(dt).astype(np.int32)
+    st[10:14] = [nb - 4, nb - 3, nb - 2, nb - 1]          # a run that ends at the pool's last block
+    dt[10:14] = [nb - 8, nb - 7, nb - 6, nb - 5]
+    seq = n * 16 - 7
+    say("allocating two 10 GiB pools")
+    src = G.device_random_pool(g, "bf16", 21)
+    dst = G.device_sentinel_pool(g)
+    w = wl.Workload("big-slab", g, g, [wl.Request(seq, st, dt)], "bf16", 21)
+    x = G.GpuTransfer(w, src, dst).run()
+    # compact copies: used blocks only, renumbered by rank
+    us, ud = np.unique(st), np.unique(dt)
+    gs_c = wl.PoolGeometry(1, len(us), 16, 8, 128, 2, wl.BHTD)
+    gd_c = wl.PoolGeometry(1, len(ud), 16, 8, 128, 2, wl.BHTD)
+    s4 = src.view(torch.int16).view(2, nb, -1)
+    d4 = dst.view(torch.int16).view(2, nb, -1)
+    src_c = s4[:, torch.from_numpy(us.astype(np.int64)).cuda()].contiguous().cpu().numpy().view(np.uint8).reshape(-1)
+    got_c = d4[:, torch.from_numpy(ud.astype(np.int64)).cuda()].contiguous().cpu().numpy().view(np.uint8).reshape(-1)
+    wc = wl.Workload("compact", gs_c, gd_c, [wl.Request(seq, np.searchsorted(us, st).astype(np.int32),
+                                                        np.searchsorted(ud, dt).astype(np.int32))], "bf16", 21)
+    want_c = wl.host_pool_sentinel(gd_c)
+    tl.oracle_pull_workload(wc, src_c, want_c)
+    G.assert_bytes_equal(got_c, want_c, "compact view of the destination")
+    # nothing outside the used blocks was written
+    touched = int((d4 != wl.SENTINEL16).sum())
+    assert touched == seq * 2 * 8 * 128
+    x.close()
+    del src, dst, s4, d4
+    torch.cuda.empty_cache()
 
 
 # ------------------------------------------------------------------ full-size configurations
