@@ -84,6 +84,9 @@ typedef struct kvd_plan kvd_plan_t;
 
 /* kvd_plan_create flags */
 #define KVD_PLAN_NO_COALESCE 1u /* keep every read transaction separate (ablation of section 4.2) */
+#define KVD_PLAN_WHOLE_BLOCKS 4u /* move every slot of a request's last block, not only the tokens below
+                                   seq_len: the block-granular transfer of section 4.1 (needs equal
+                                   block sizes, else KVD_ERR_MISMATCH)                              */
 #define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a fixed grid that loops over the work items instead
                                    of one small workgroup per work item (for comparison; slower)  */
 
@@ -133,6 +136,9 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out);
  * handles may be freed before the plan.  Device and pinned scratch memory (a few bytes per
  * block) is allocated by the first kvd_build_descriptors that passes validation, on the
  * device that is current then.
+ * When K and V of a block are neighbours in memory on both sides (stride_kv equals the elements
+ * of one block) and the inner order is the same, a block's K and V are one byte range and merge
+ * like any other contiguous ranges (section 4.1).
  * Errors: KVD_ERR_INVALID (null, zero capacity), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
  * elem_bytes differ; block sizes of which neither divides the other), KVD_ERR_ALIAS (the byte
  * ranges of the two pools overlap).

@@ -153,8 +153,10 @@ static int cmp_txn_remote(const void *a, const void *b)
 }
 
 /*
- * Read transactions of one request for one tensor and one of K / V, in the
- * order the blocks are handed to Transfer().  A transaction is a maximal byte
+ * Read transactions of one request for one tensor, in the order the blocks
+ * are handed to Transfer(): for kv = 0 or 1 only the K or only the V half, for
+ * kv < 0 both, K then V of every block (a block "consists of the K and V" and
+ * gives one transaction for each, section 4.1).  A transaction is a maximal byte
  * range that is contiguous on both sides and holds only tokens of the request
  * (only tokens below seq_len move).  They are found the slow way: list every
  * element of a (source block, destination block) pair with both its offsets,
@@ -184,26 +186,28 @@ int64_t kvdo_request_transactions(const kvdo_tensor *s, const kvdo_tensor *d, in
         int64_t t1 = t0 + 1;
         while (t1 < seq_len && t1 / Ls == t0 / Ls && t1 / Ld == t0 / Ld)
             ++t1;
-        int64_t n = 0;
-        for (int64_t t = t0; t < t1; ++t)
-            for (int64_t h = 0; h < H; ++h)
-                for (int64_t x = 0; x < D; ++x) {
-                    elems[n].remote = offset_by_role(s, sa, src_table[t / Ls], kv, t % Ls, h, x);
-                    elems[n].local = offset_by_role(d, da, dst_table[t / Ld], kv, t % Ld, h, x);
-                    elems[n].size = e;
-                    ++n;
+        for (int64_t part = (kv < 0 ? 0 : kv); part <= (kv < 0 ? 1 : kv); ++part) {
+            int64_t n = 0;
+            for (int64_t t = t0; t < t1; ++t)
+                for (int64_t h = 0; h < H; ++h)
+                    for (int64_t x = 0; x < D; ++x) {
+                        elems[n].remote = offset_by_role(s, sa, src_table[t / Ls], part, t % Ls, h, x);
+                        elems[n].local = offset_by_role(d, da, dst_table[t / Ld], part, t % Ld, h, x);
+                        elems[n].size = e;
+                        ++n;
+                    }
+            qsort(elems, (size_t)n, sizeof(kvdo_txn), cmp_txn_remote);
+            for (int64_t i = 0; i < n; ++i) {
+                if (i > 0 && out[n_out - 1].remote + out[n_out - 1].size == elems[i].remote &&
+                    out[n_out - 1].local + out[n_out - 1].size == elems[i].local) {
+                    out[n_out - 1].size += elems[i].size;
+                } else {
+                    if (n_out == cap) {
+                        free(elems);
+                        return -1;
+                    }
+                    out[n_out++] = elems[i];
                 }
-        qsort(elems, (size_t)n, sizeof(kvdo_txn), cmp_txn_remote);
-        for (int64_t i = 0; i < n; ++i) {
-            if (i > 0 && out[n_out - 1].remote + out[n_out - 1].size == elems[i].remote &&
-                out[n_out - 1].local + out[n_out - 1].size == elems[i].local) {
-                out[n_out - 1].size += elems[i].size;
-            } else {
-                if (n_out == cap) {
-                    free(elems);
-                    return -1;
-                }
-                out[n_out++] = elems[i];
             }
         }
         t0 = t1;

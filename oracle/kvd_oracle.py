@@ -147,12 +147,13 @@ def pull(src: Sequence[Tensor], dst: Sequence[Tensor], layer_begin: int, layer_e
 
 
 def request_transactions(s: Tensor, d: Tensor, kv: int, src_table, dst_table, seq_len: int) -> np.ndarray:
-    """Read transactions (remote offset, local offset, size) of one request for one tensor."""
+    """Read transactions (remote offset, local offset, size) of one request for one tensor:
+    kv = 0 / 1 for its K / V half, kv = -1 for both in Transfer() order (K then V of every block)."""
     st, dt = _table(src_table), _table(dst_table)
     ls = s.shape[s.dims.index(L)]
     ld = d.shape[d.dims.index(L)]
     hh = s.shape[s.dims.index(H)]
-    cap = (len(st) + len(dt) + 2) * max(1, hh) * max(ls, ld) + 8
+    cap = 2 * (len(st) + len(dt) + 2) * max(1, hh) * max(ls, ld) + 8
     out = (_Txn * cap)()
     cs, cd = s.c(), d.c()
     n = lib().kvdo_request_transactions(

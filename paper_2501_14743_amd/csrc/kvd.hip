@@ -100,6 +100,7 @@ struct Geo {
     uint32_t hk, du;                    // KV heads; 16-byte units per (token, head) row
     uint32_t piece_tokens;              // min(tb_src, tb_dst): tokens that share a block on both sides
     uint32_t rows_per_item;             // re-layout: (token, head) rows per work item = 256 / du
+    uint32_t kv_shift;                  // 1: K and V are separate slabs; 0: K/V folded into the head axis
     uint32_t mode;
     FastDiv div_du, div_hk, div_tb_src, div_tb_dst;
 };
@@ -378,7 +379,7 @@ struct PullArgs {
     unsigned char *dst_base;
     const Item *items;
     const Header *hdr;  // descriptor and work-item counts, written by the build kernel
-    uint32_t slabs;     // 2 * the largest layer count of any request
+    uint32_t slabs;     // (K, V slabs) * the largest layer count of any request
 };
 
 // Streaming 16-byte store: non-temporal at device scope.  Measured on MI355X, this cache policy
@@ -393,7 +394,7 @@ __device__ __forceinline__ void stream_store(u32x4 v, u32x4 *p)
 __device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const Item it, uint32_t y,
                                           uint32_t u)
 {
-    if (y >= (it.layers >> 16) * 2) return;
+    if (y >= (it.layers >> 16) << g.kv_shift) return;
     uint32_t s16, d16;
     if (g.mode < kRelayoutHT2TH) {
         if (u >= it.n) return;
@@ -408,7 +409,7 @@ __device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const
         s16 = it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
         d16 = it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
     }
-    const uint32_t layer = (it.layers & 0xFFFFu) + (y >> 1), kv = y & 1u;
+    const uint32_t layer = (it.layers & 0xFFFFu) + (y >> g.kv_shift), kv = y & g.kv_shift;
     const unsigned char *sp = a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
     unsigned char *dp = a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
     const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(sp + (size_t)s16 * kUnitBytes));
@@ -700,11 +701,33 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     g.hk = s.num_kv_heads;
     g.du = (uint32_t)((uint64_t)s.head_dim * e / kUnitBytes);
     g.piece_tokens = tmin;
-    g.rows_per_item = kChunkUnits / g.du;
-    if (s.layout == d.layout || g.hk == 1)
+    g.kv_shift = 1;
+    const bool same_inner = s.layout == d.layout || g.hk == 1;
+    const bool kv_adjacent = (uint64_t)s.stride_kv == (uint64_t)s.block_tokens * s.num_kv_heads * s.head_dim &&
+                             (uint64_t)d.stride_kv == (uint64_t)d.block_tokens * d.num_kv_heads * d.head_dim;
+    if (same_inner && kv_adjacent) {
+        // K and V of a block are neighbours on both sides: fold K/V into the head axis, so that a
+        // block's K and V form one byte range and can merge (section 4.1: contiguity is a matter
+        // of offsets).  [kv][head][token][dim] is 2*heads planes; [kv][token][head][dim] is 2
+        // planes of (heads*dim)-wide rows.
+        if (s.layout == KVD_LAYOUT_BTHD && g.hk > 1) {
+            g.du *= g.hk;
+            g.hk = 2;
+        } else {
+            g.hk *= 2;
+        }
+        g.kv_shift = 0;
+        g.mode = kSpanHeadMajor;
+    } else if (same_inner) {
         g.mode = (s.layout == KVD_LAYOUT_BTHD || g.hk == 1) ? kSpanTokenMajor : kSpanHeadMajor;
-    else
+    } else {
         g.mode = (s.layout == KVD_LAYOUT_BHTD) ? kRelayoutHT2TH : kRelayoutTH2HT;
+    }
+    g.rows_per_item = g.du <= kChunkUnits ? kChunkUnits / g.du : 0;
+    if ((flags & KVD_PLAN_WHOLE_BLOCKS) && s.block_tokens != d.block_tokens) {
+        delete p;
+        return fail(KVD_ERR_MISMATCH, "whole-block transfers need equal block sizes");
+    }
     g.div_du = make_fastdiv(g.du);
     g.div_hk = make_fastdiv(g.hk);
     g.div_tb_src = make_fastdiv(g.tb_src);
@@ -762,10 +785,15 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
     if (!src_tbls || !dst_tbls || !n_src || !n_dst || !seq_lens) return fail(KVD_ERR_INVALID, "null argument");
     const Geo &g = p->geo;
 
+    // whole-block mode moves every slot of the last block too (the block-granular transfer of
+    // section 4.1); block sizes are equal then
+    const bool whole = (p->flags & KVD_PLAN_WHOLE_BLOCKS) != 0;
+    auto effective_len = [&](uint32_t seq_len) { return whole ? ceil_div(seq_len, g.tb_src) * g.tb_src : seq_len; };
+
     // 1. everything that can be checked without touching the plan
     uint64_t add_src = 0, add_dst = 0, add_txn = 0, add_items = 0, add_reqs = 0;
     for (uint32_t k = 0; k < n_requests; ++k) {
-        const uint32_t seq_len = seq_lens[k];
+        const uint32_t seq_len = effective_len(seq_lens[k]);
         if (seq_len == 0) continue;
         const int32_t *st = src_tbls[k], *dt = dst_tbls[k];
         if (!st || !dt) return fail(KVD_ERR_INVALID, "request %u: null block table", k);
@@ -828,7 +856,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
     const bool same_layers = first_new > 0 && p->reqs.back().layer_begin == layer_begin &&
                              p->reqs.back().layer_end == layer_end;
     for (uint32_t k = 0; k < n_requests; ++k) {
-        const uint32_t seq_len = seq_lens[k];
+        const uint32_t seq_len = effective_len(seq_lens[k]);
         if (seq_len == 0) continue;
         ReqHost r;
         r.table_off_src = (uint32_t)p->used_src;
@@ -843,7 +871,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         for (uint32_t i = 0; i < r.n_dst; ++i) p->dst_used[(uint32_t)dst_tbls[k][i]] = 1;
         p->used_src += r.n_src;
         p->used_dst += r.n_dst;
-        p->payload_bytes += (uint64_t)seq_len * (layer_end - layer_begin) * 2 * g.hk * g.du * kUnitBytes;
+        p->payload_bytes += ((uint64_t)seq_len * (layer_end - layer_begin) * g.hk * g.du * kUnitBytes) << g.kv_shift;
         p->reqs.push_back(r);
     }
     p->max_layers = std::max(p->max_layers, layer_end - layer_begin);
@@ -905,7 +933,7 @@ int kvd_pull(kvd_plan_t *p, void *stream)
     a.dst_base = (unsigned char *)p->dst.base;
     a.items = p->items_dev;
     a.hdr = p->hdr_dev;
-    a.slabs = p->max_layers * 2;
+    a.slabs = p->max_layers << p->geo.kv_shift;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
         const uint32_t grid = (uint32_t)p->num_cus * (2048 / T);
@@ -935,7 +963,7 @@ int kvd_pull_blockwise_memcpy(kvd_plan_t *p, void *stream)
     for (const ReqHost &r : p->reqs) {
         const uint32_t whole = r.seq_len / g.tb_src, tail = r.seq_len % g.tb_src;
         for (uint32_t layer = r.layer_begin; layer < r.layer_end; ++layer)
-            for (uint32_t kv = 0; kv < 2; ++kv) {
+            for (uint32_t kv = 0; kv < (1u << g.kv_shift); ++kv) {
                 const uint64_t so = layer * g.src_layer_bytes + kv * g.src_kv_bytes;
                 const uint64_t dof = layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
                 for (uint32_t b = 0; b < whole; ++b) {

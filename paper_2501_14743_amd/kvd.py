@@ -22,6 +22,7 @@ KVD_ERR_ALIAS, KVD_ERR_CAPACITY, KVD_ERR_HIP = -4, -5, -6
 KVD_LAYOUT_BHTD, KVD_LAYOUT_BTHD = 0, 1
 KVD_PLAN_NO_COALESCE = 1
 KVD_PLAN_PERSISTENT = 2
+KVD_PLAN_WHOLE_BLOCKS = 4
 LAYOUTS = {"BHTD": KVD_LAYOUT_BHTD, "BTHD": KVD_LAYOUT_BTHD}
 
 

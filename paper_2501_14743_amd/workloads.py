@@ -26,7 +26,8 @@ BTHD = "BTHD"  # inside a block: [token][head][dim]
 
 @dataclass(frozen=True)
 class PoolGeometry:
-    """One paged pool, stored as a single dense allocation [layer][kv][block][inner]."""
+    """One paged pool, stored as a single dense allocation [layer][kv][block][inner], or
+    [layer][block][kv][inner] when kv_adjacent (K and V of a block next to each other)."""
     num_layers: int
     num_blocks: int
     block_tokens: int
@@ -34,6 +35,7 @@ class PoolGeometry:
     head_dim: int
     elem_bytes: int
     layout: str = BHTD
+    kv_adjacent: bool = False
 
     @property
     def tile_elems(self) -> int:
@@ -41,15 +43,15 @@ class PoolGeometry:
 
     @property
     def stride_block(self) -> int:
-        return self.tile_elems
+        return (2 if self.kv_adjacent else 1) * self.tile_elems
 
     @property
     def stride_kv(self) -> int:
-        return self.num_blocks * self.tile_elems
+        return self.tile_elems if self.kv_adjacent else self.num_blocks * self.tile_elems
 
     @property
     def stride_layer(self) -> int:
-        return 2 * self.stride_kv
+        return 2 * self.num_blocks * self.tile_elems
 
     @property
     def total_elems(self) -> int:

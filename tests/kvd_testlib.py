@@ -45,7 +45,8 @@ def oracle_pull_workload(w: wl.Workload, src_bytes: np.ndarray, dst_bytes: np.nd
 
 
 def oracle_plan_descriptors(w: wl.Workload, layer: int, kv: int) -> np.ndarray:
-    """Coalesced read transactions of the whole batch for one (layer, K/V) tensor:
+    """Coalesced read transactions of the whole batch for one (layer, K/V) tensor, or with
+    kv = -1 for the layer's whole tensor (K then V of every block):
     every request's transactions queued in order, then merged (section 4.2)."""
     s = oracle_tensors(w.src, None)[layer]
     d = oracle_tensors(w.dst, None)[layer]

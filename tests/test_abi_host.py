@@ -76,6 +76,8 @@ def test_plan_create_rejects_mismatch_and_overlap():
     expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(block_tokens=24)), 1, 8)
     expect(kvd.KVD_ERR_ALIAS, kvd.Plan, s, s, 1, 8)
     expect(kvd.KVD_ERR_ALIAS, kvd.Plan, s, kvd.Pool(FAKE_SRC + g.total_bytes - 4096, g), 1, 8)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(block_tokens=32, num_blocks=32)), 1, 8,
+           kvd.KVD_PLAN_WHOLE_BLOCKS)
     expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 0, 8)
     expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 1, 0)
     # touching but not overlapping is fine

@@ -354,6 +354,64 @@ def test_plain_copy():
         kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr() + 1, 16)
 
 
+def _frag_request(gs, gd, tokens, seed):
+    rng = np.random.default_rng(seed)
+    return wl.Request(tokens,
+                      wl.fragmented_allocation(rng, np.ones(gs.num_blocks, bool), wl.blocks_for(tokens, gs.block_tokens), 6),
+                      wl.fragmented_allocation(rng, np.ones(gd.num_blocks, bool), wl.blocks_for(tokens, gd.block_tokens), 6))
+
+
+@pytest.mark.parametrize("gs,gd", [
+    (small_geom(kv_adjacent=True), small_geom(kv_adjacent=True)),
+    (small_geom(kv_adjacent=True, layout=wl.BTHD), small_geom(kv_adjacent=True, layout=wl.BTHD)),
+    (small_geom(kv_adjacent=True, layout=wl.BTHD), small_geom(kv_adjacent=True, layout=wl.BTHD, block_tokens=32, num_blocks=48)),
+    (small_geom(kv_adjacent=True, block_tokens=32, num_blocks=48), small_geom(kv_adjacent=True, block_tokens=8, num_blocks=192)),
+    (small_geom(kv_adjacent=True, num_kv_heads=1), small_geom(kv_adjacent=True, num_kv_heads=1, layout=wl.BTHD)),
+], ids=["hm", "tm", "tm16-32", "hm32-8", "one-head"])
+@pytest.mark.parametrize("tokens", [333, 1024])
+def test_pools_with_k_and_v_of_a_block_adjacent(gs, gd, tokens):
+    """K and V of a block merge into one range (byte-offset contiguity, section 4.1)."""
+    w = wl.Workload("kv-adjacent", gs, gd, [_frag_request(gs, gd, tokens, 31)], "bf16", 31)
+    x = G.run_and_compare(w, host_src(w))
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    want = tl.oracle_plan_descriptors(w, 0, -1)
+    assert np.array_equal(got, want)
+    if gs.block_tokens == gd.block_tokens and tokens % 16 == 0:
+        # whole blocks only: every run of r consecutive blocks is ONE descriptor of 2*r tiles
+        r = w.requests[0]
+        breaks = np.count_nonzero((r.src_table[1:] != r.src_table[:-1] + 1) | (r.dst_table[1:] != r.dst_table[:-1] + 1))
+        assert len(got) == 1 + breaks and got[:, 2].sum() == 2 * tokens * gs.num_kv_heads * gs.head_dim * 2
+    x.close()
+
+
+@pytest.mark.parametrize("adj_src,adj_dst", [(True, False), (False, True)])
+def test_one_side_with_adjacent_k_and_v(adj_src, adj_dst):
+    gs, gd = small_geom(kv_adjacent=adj_src), small_geom(kv_adjacent=adj_dst)
+    w = wl.Workload("kv-one-side", gs, gd, [_frag_request(gs, gd, 700, 32)], "bf16", 32)
+    x = G.run_and_compare(w, host_src(w))
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), tl.oracle_plan_descriptors(w, 0, 0))
+    x.close()
+
+
+@pytest.mark.parametrize("g", [small_geom(), small_geom(layout=wl.BTHD), small_geom(kv_adjacent=True)],
+                         ids=["hm", "tm", "kv-adjacent"])
+def test_whole_block_mode_moves_every_slot_of_the_last_block(g):
+    tokens = 16 * 9 + 5
+    w = wl.Workload("whole", g, g, [_frag_request(g, g, tokens, 33)], "bf16", 33)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_WHOLE_BLOCKS).run()
+    # block-granular transfer = the definition applied to all 16 slots of the 10 blocks
+    r = w.requests[0]
+    w_full = wl.Workload("whole-oracle", g, g, [wl.Request(160, r.src_table, r.dst_table)], "bf16", 33)
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w_full, src_host), "whole-block mode")
+    st = x.plan.stats(x.stream.cuda_stream)
+    assert st["payload_bytes"] == 160 * g.num_layers * 2 * g.num_kv_heads * g.head_dim * 2
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream),
+                          tl.oracle_plan_descriptors(w_full, 0, -1 if g.kv_adjacent else 0))
+    x.close()
+
+
 @pytest.mark.parametrize("gs,gd", [
     (wl.PoolGeometry(2, 6, 1024, 2, 8, 2, wl.BHTD), wl.PoolGeometry(2, 24, 256, 2, 8, 2, wl.BTHD)),
     (wl.PoolGeometry(2, 6, 1024, 3, 8, 2, wl.BTHD), wl.PoolGeometry(2, 6, 1024, 3, 8, 2, wl.BHTD)),

@@ -48,6 +48,7 @@ def pin_checks():
               pins.test_span_size_matches_paper, pins.test_span_size_follows_largest_stride_axis,
               pins.test_block8_is_two_transactions_and_blocks01_merge,
               pins.test_partial_last_block_moves_only_the_request_tokens,
+              pins.test_adjacent_k_and_v_are_queued_k_first_and_merge,
               pins.test_queue_example_merges_across_requests, pins.test_merge_needs_both_sides_contiguous,
               lambda: pins.test_run_count_closed_form(0), pins.test_sizes_quoted_in_paper,
               pins.test_round_trip_is_identity_on_valid_tokens, pins.test_identity_tables_reduce_to_memcpy]

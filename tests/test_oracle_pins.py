@@ -92,6 +92,25 @@ def test_partial_last_block_moves_only_the_request_tokens():
     assert len(orc.request_transactions(hm, hm, 0, [1, 2], [3, 4], 32)) == 2
 
 
+def test_adjacent_k_and_v_are_queued_k_first_and_merge():
+    # the paper's tensor keeps K and V 10 sub-tensors apart: K then V, two transactions that stay two
+    t = paper_tensor()
+    q = orc.request_transactions(t, t, -1, [8], [8], 16)
+    assert q.tolist() == [[65536, 65536, 8192], [147456, 147456, 8192]]
+    assert len(orc.coalesce(q)) == 2
+    # same shapes, but V of a block right behind its K (stride of KV = one sub-tensor)
+    adj = orc.Tensor(None, 0, [orc.B, orc.KV, orc.L, orc.H, orc.D], [10, 2, 16, 2, 128],
+                     [8192, 4096, 256, 128, 1], 2)
+    q = orc.request_transactions(adj, adj, -1, [3, 4], [6, 7], 32)
+    assert q.tolist() == [[3 * 16384, 6 * 16384, 8192], [3 * 16384 + 8192, 6 * 16384 + 8192, 8192],
+                          [4 * 16384, 7 * 16384, 8192], [4 * 16384 + 8192, 7 * 16384 + 8192, 8192]]
+    assert orc.coalesce(q).tolist() == [[3 * 16384, 6 * 16384, 4 * 8192]]
+    # a partial block: the K part and the V part are apart again
+    q = orc.request_transactions(adj, adj, -1, [3], [6], 5)
+    assert q.tolist() == [[3 * 16384, 6 * 16384, 2560], [3 * 16384 + 8192, 6 * 16384 + 8192, 2560]]
+    assert len(orc.coalesce(q)) == 2
+
+
 # ---------------------------------------------------------------- section 4.2 queue example
 
 def test_queue_example_merges_across_requests():
