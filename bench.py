@@ -181,6 +181,17 @@ def main() -> int:
         y.build()
         extras["persistent_grid_pull_us"] = timed(lambda: y.plan.pull(sh), 10)
         y.close()
+        # the buffer-based scheme: gather kernel -> copy -> host wait -> scatter kernel -> host wait, with a
+        # staging buffer that holds two blocks (the paper's figure) and one that holds 64 MiB
+        tile = w.src.tile_elems * w.src.elem_bytes
+        for label, nbytes in (("two_blocks", max(4096, 2 * tile)), ("64MiB", 64 << 20)):
+            sb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            rb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            x.plan.pull_staged(sb.data_ptr(), rb.data_ptr(), nbytes, sh)
+            extras[f"staged_{label}_buffer_us"] = (time.perf_counter() - t) * 1e6
+            del sb, rb
         # one hipMemcpyAsync per (layer, K/V, block)
         if not stats["relayout"]:
             torch.cuda.synchronize()

@@ -200,6 +200,19 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
 int kvd_pull(kvd_plan_t *plan, void *stream);
 
 /*
+ * Reported baseline, not the product path: the buffer-based transfer the paper argues against
+ * (section 4.1, message-based scheme).  Per iteration, as many 4 KiB work items of one (layer,
+ * K/V) as `buffer_bytes` holds are gathered by a kernel into `send_buffer`, copied to
+ * `recv_buffer` (standing in for the wire), waited for by the host, scattered by a second kernel
+ * into the destination pool, and waited for again (the notification).  Both buffers are DEVICE
+ * memory of at least buffer_bytes (>= 4096), owned by the caller.  Moves the same bytes as
+ * kvd_pull with three times the memory traffic and two host waits per iteration.  Blocks the
+ * calling thread until the transfer is complete.
+ */
+int kvd_pull_staged(kvd_plan_t *plan, void *send_buffer, void *recv_buffer, uint64_t buffer_bytes,
+                    void *stream);
+
+/*
  * Reported baseline, not the product path: the same transfer as one hipMemcpyAsync per
  * (request, layer, K/V, block) on `stream`, the way a per-block message scheme touches memory
  * (section 3, motivation 1).  Only for pools with equal layout and block size

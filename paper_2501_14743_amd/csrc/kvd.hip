@@ -390,30 +390,69 @@ __device__ __forceinline__ void stream_store(u32x4 v, u32x4 *p)
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
 
-// One 16-byte unit of work item `it` for slab `y` (= 2 * layer offset + kv): lane unit u.
-__device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const Item it, uint32_t y,
-                                          uint32_t u)
+// Where lane unit u of work item `it` sits on both sides, in 16-byte units from the slab base.
+// False if the item has no such unit or does not take part in slab y.
+__device__ __forceinline__ bool unit_offsets(const Geo &g, const Item it, uint32_t y, uint32_t u,
+                                             uint32_t *s16, uint32_t *d16)
 {
-    if (y >= (it.layers >> 16) << g.kv_shift) return;
-    uint32_t s16, d16;
+    if (y >= (it.layers >> 16) << g.kv_shift) return false;
     if (g.mode < kRelayoutHT2TH) {
-        if (u >= it.n) return;
-        s16 = it.src16 + u;
-        d16 = it.dst16 + u;
+        if (u >= it.n) return false;
+        *s16 = it.src16 + u;
+        *d16 = it.dst16 + u;
     } else {
         const uint32_t r = fdiv(u, g.div_du), x = u - r * g.du;
-        if (r > (it.n >> 20)) return;
+        if (r > (it.n >> 20)) return false;
         const uint32_t row = (it.n & 0xFFFFFu) + r;
         const uint32_t tok = fdiv(row, g.div_hk), head = row - tok * g.hk;
         const uint32_t in_ht_src = head * g.tb_src + tok, in_ht_dst = head * g.tb_dst + tok;
-        s16 = it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
-        d16 = it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
+        *s16 = it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
+        *d16 = it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
     }
+    return true;
+}
+
+__device__ __forceinline__ const unsigned char *src_slab(const Geo &g, const PullArgs &a, const Item it, uint32_t y)
+{
     const uint32_t layer = (it.layers & 0xFFFFu) + (y >> g.kv_shift), kv = y & g.kv_shift;
-    const unsigned char *sp = a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
-    unsigned char *dp = a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
+    return a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
+}
+
+__device__ __forceinline__ unsigned char *dst_slab(const Geo &g, const PullArgs &a, const Item it, uint32_t y)
+{
+    const uint32_t layer = (it.layers & 0xFFFFu) + (y >> g.kv_shift), kv = y & g.kv_shift;
+    return a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
+}
+
+// One 16-byte unit of work item `it` for slab `y` (= layer offset, K/V): lane unit u.
+__device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const Item it, uint32_t y,
+                                          uint32_t u)
+{
+    uint32_t s16, d16;
+    if (!unit_offsets(g, it, y, u, &s16, &d16)) return;
+    const unsigned char *sp = src_slab(g, a, it, y);
+    unsigned char *dp = dst_slab(g, a, it, y);
     const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(sp + (size_t)s16 * kUnitBytes));
     stream_store(v, (u32x4 *)(dp + (size_t)d16 * kUnitBytes));
+}
+
+// Message-style baseline (section 4.1, the buffer-based transfer the paper compares against): work
+// items [first_item, first_item + n) of slab y are packed into a contiguous buffer (GATHER) or
+// unpacked from one (scatter), 4 KiB per item.
+template <bool GATHER>
+__global__ __launch_bounds__(64) void kvd_stage_kernel(Geo g, PullArgs a, unsigned char *buffer,
+                                                       uint32_t first_item, uint32_t n, uint32_t y)
+{
+    const uint32_t c = blockIdx.x >> 2, u = (blockIdx.x & 3u) * 64 + threadIdx.x;
+    if (c >= n) return;
+    const Item it = a.items[first_item + c];
+    uint32_t s16, d16;
+    if (!unit_offsets(g, it, y, u, &s16, &d16)) return;
+    u32x4 *packed = (u32x4 *)(buffer + ((size_t)c * kChunkUnits + u) * kUnitBytes);
+    if (GATHER)
+        *packed = *(const u32x4 *)(src_slab(g, a, it, y) + (size_t)s16 * kUnitBytes);
+    else
+        *(u32x4 *)(dst_slab(g, a, it, y) + (size_t)d16 * kUnitBytes) = *packed;
 }
 
 // Which piece (T consecutive units of a work item) workgroup `b` of a slab's row of the grid moves.
@@ -946,6 +985,42 @@ int kvd_pull(kvd_plan_t *p, void *stream)
                            p->geo, a);
     }
     KVD_HIP(hipGetLastError());
+    return KVD_OK;
+}
+
+int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_t buffer_bytes, void *stream)
+{
+    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
+    if (!send_buffer || !recv_buffer) return fail(KVD_ERR_INVALID, "null buffer");
+    if (buffer_bytes < 4096 || ((uintptr_t)send_buffer % 16) || ((uintptr_t)recv_buffer % 16))
+        return fail(KVD_ERR_INVALID, "buffers must hold at least 4096 bytes and be 16-byte aligned");
+    if (p->reqs.empty()) return KVD_OK;
+    hipStream_t st = (hipStream_t)stream;
+    KVD_HIP(hipStreamSynchronize(st));
+    Header h;
+    KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
+    PullArgs a;
+    a.src_base = (const unsigned char *)p->src.base;
+    a.dst_base = (unsigned char *)p->dst.base;
+    a.items = p->items_dev;
+    a.hdr = p->hdr_dev;
+    a.slabs = p->max_layers << p->geo.kv_shift;
+    const uint32_t cap = (uint32_t)std::min<uint64_t>(buffer_bytes / 4096, 1u << 20);
+    for (uint32_t y = 0; y < a.slabs; ++y)
+        for (uint32_t c0 = 0; c0 < h.n_items; c0 += cap) {
+            const uint32_t n = std::min(cap, h.n_items - c0);
+            // prefill side: gather into the send buffer; "send" it; the CPU waits for the GPU
+            hipLaunchKernelGGL(kvd_stage_kernel<true>, dim3(n * 4), dim3(64), 0, st, p->geo, a,
+                               (unsigned char *)send_buffer, c0, n, y);
+            KVD_HIP(hipGetLastError());
+            KVD_HIP(hipMemcpyAsync(recv_buffer, send_buffer, (size_t)n * 4096, hipMemcpyDeviceToDevice, st));
+            KVD_HIP(hipStreamSynchronize(st));
+            // decode side: scatter out of the receive buffer, then notify (another wait)
+            hipLaunchKernelGGL(kvd_stage_kernel<false>, dim3(n * 4), dim3(64), 0, st, p->geo, a,
+                               (unsigned char *)recv_buffer, c0, n, y);
+            KVD_HIP(hipGetLastError());
+            KVD_HIP(hipStreamSynchronize(st));
+        }
     return KVD_OK;
 }
 

@@ -85,6 +85,7 @@ def lib() -> ctypes.CDLL:
                                               u32, u32, vp]
     L.kvd_pull.argtypes = [vp, vp]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
+    L.kvd_pull_staged.argtypes = [vp, vp, vp, u64, vp]
     L.kvd_plan_reset.argtypes = [vp]
     L.kvd_plan_stats.argtypes = [vp, vp, ctypes.POINTER(kvd_stats_t)]
     L.kvd_plan_get_descriptors.argtypes = [vp, vp, ctypes.POINTER(kvd_span_t), ctypes.POINTER(kvd_piece_t),
@@ -93,7 +94,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
-                 "kvd_pull_blockwise_memcpy", "kvd_plan_reset", "kvd_plan_stats",
+                 "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -162,6 +163,10 @@ def kvd_pull(plan: int, stream: int = 0) -> None:
 
 def kvd_pull_blockwise_memcpy(plan: int, stream: int = 0) -> None:
     _check(lib().kvd_pull_blockwise_memcpy(plan, stream))
+
+
+def kvd_pull_staged(plan: int, send_buffer: int, recv_buffer: int, buffer_bytes: int, stream: int = 0) -> None:
+    _check(lib().kvd_pull_staged(plan, send_buffer, recv_buffer, buffer_bytes, stream))
 
 
 def kvd_plan_reset(plan: int) -> None:
@@ -242,6 +247,9 @@ class Plan:
 
     def pull_blockwise_memcpy(self, stream=0):
         kvd_pull_blockwise_memcpy(self.handle, stream)
+
+    def pull_staged(self, send_buffer, recv_buffer, buffer_bytes, stream=0):
+        kvd_pull_staged(self.handle, send_buffer, recv_buffer, buffer_bytes, stream)
 
     def reset(self):
         kvd_plan_reset(self.handle)

@@ -343,6 +343,24 @@ def test_blockwise_memcpy_baseline_gives_the_same_bytes():
     y.close()
 
 
+@pytest.mark.parametrize("w", [wl.config2(num_layers=2, pool_blocks=512, tokens=1000),
+                               wl.config5(num_layers=2, src_pool_blocks=128, tokens=500),
+                               wl.config3(num_layers=1, num_requests=6, median=100.0, hi=600)], ids=lambda w: w.name)
+@pytest.mark.parametrize("buffer_bytes", [4096, 65536, 1 << 22])
+def test_staged_gather_scatter_baseline_gives_the_same_bytes(w, buffer_bytes):
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    send = torch.zeros(buffer_bytes, dtype=torch.uint8, device="cuda")
+    recv = torch.zeros(buffer_bytes, dtype=torch.uint8, device="cuda")
+    x = G.GpuTransfer(w, src, dst)
+    x.build()
+    x.plan.pull_staged(send.data_ptr(), recv.data_ptr(), buffer_bytes, x.stream.cuda_stream)
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "staged baseline")
+    with pytest.raises(kvd.KvdError):
+        x.plan.pull_staged(send.data_ptr(), recv.data_ptr(), 100, x.stream.cuda_stream)
+    x.close()
+
+
 def test_plain_copy():
     n = (1 << 24) + 4096 + 16
     a = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
