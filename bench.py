@@ -192,6 +192,43 @@ def main() -> int:
             x.plan.pull_staged(sb.data_ptr(), rb.data_ptr(), nbytes, sh)
             extras[f"staged_{label}_buffer_us"] = (time.perf_counter() - t) * 1e6
             del sb, rb
+        # push-mode-like use (section 4.3): one layer per launch, as a prefill worker would issue them,
+        # alone and next to a compute-bound kernel on another stream
+        if len(w.requests) == 1 and not stats["relayout"]:
+            r = w.requests[0]
+            layers = range(w.layer_begin, w.layer_end)
+
+            def per_layer():
+                for layer in layers:
+                    x.plan.reset()
+                    x.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, layer, layer + 1, sh)
+                    x.plan.pull(sh)
+            per_layer()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            per_layer()
+            torch.cuda.synchronize()
+            extras["per_layer_launches_total_us"] = (time.perf_counter() - t) * 1e6
+            ma = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
+            mb = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
+
+            def gemms(n):
+                for _ in range(n):
+                    torch.matmul(ma, mb)
+            gemms(2)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            gemms(10)
+            torch.cuda.synchronize()
+            extras["ten_gemms_alone_us"] = (time.perf_counter() - t) * 1e6
+            t = time.perf_counter()
+            gemms(10)
+            per_layer()
+            torch.cuda.synchronize()
+            extras["ten_gemms_with_per_layer_pulls_us"] = (time.perf_counter() - t) * 1e6
+            del ma, mb
+            x.plan.reset()
+            x.build(batch)
         # one hipMemcpyAsync per (layer, K/V, block)
         if not stats["relayout"]:
             torch.cuda.synchronize()
