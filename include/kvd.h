@@ -87,8 +87,9 @@ typedef struct kvd_plan kvd_plan_t;
 #define KVD_PLAN_WHOLE_BLOCKS 4u /* move every slot of a request's last block, not only the tokens below
                                    seq_len: the block-granular transfer of section 4.1 (needs equal
                                    block sizes, else KVD_ERR_MISMATCH)                              */
-#define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a fixed grid that loops over the work items instead
-                                   of one small workgroup per work item (for comparison; slower)  */
+#define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a persistent grid that stages the coalesced descriptors
+                                   in LDS and walks them wave by wave, instead of one small workgroup
+                                   per work item (for comparison; slower; one layer range per plan) */
 
 /* A coalesced read transaction of the byte-copy path, relative to (layer 0, K): the copy for
  * (layer, kv) adds layer*stride_layer*elem_bytes + kv*stride_kv*elem_bytes of the respective

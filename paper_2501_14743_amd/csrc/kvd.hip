@@ -10,8 +10,9 @@
 //                      16-byte load and one 16-byte store per lane, non-temporal.  The
 //                      hardware dispatcher hands the work items out in table order, which
 //                      keeps the traffic an orderly sweep; measured on MI355X this beats a
-//                      persistent grid that loops over the same items.
-//   kvd_pull_loop_kernel  the persistent-grid form of the same copy (kept for comparison).
+//                      persistent grid that walks LDS-staged descriptors.
+//   kvd_pull_persistent_kernel  persistent grid with the descriptors staged in LDS (kept for
+//                      comparison).
 //   kvd_copy_kernel    plain streaming copy (counter calibration / practical ceiling).
 //
 // Descriptors and work items are relative to the (layer 0, K) slab; the pull kernel adds the
@@ -191,6 +192,29 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, const 
     return t;
 }
 
+// Work item number cl of descriptor d.
+__device__ __forceinline__ Item make_item(const Geo &g, const Desc d, uint32_t cl, uint32_t layers)
+{
+    Item it;
+    it.layers = layers;
+    if (g.mode < kRelayoutHT2TH) {
+        it.src16 = d.src16 + cl * kChunkUnits;
+        it.dst16 = d.dst16 + cl * kChunkUnits;
+        it.n = min(kChunkUnits, d.a - d.src16 - cl * kChunkUnits);
+    } else {
+        const uint32_t st0 = d.a & 1023u, dt0 = (d.a >> 10) & 1023u, ntok = d.a >> 20;
+        const uint32_t row0 = cl * g.rows_per_item;
+        const uint32_t rows = min(g.rows_per_item, ntok * g.hk - row0);
+        // fold the first token's slot into the bases (both layouts are linear in the slot)
+        const uint32_t s_tok = (g.mode == kRelayoutHT2TH) ? g.du : g.hk * g.du;
+        const uint32_t d_tok = (g.mode == kRelayoutHT2TH) ? g.hk * g.du : g.du;
+        it.src16 = d.src16 + st0 * s_tok;
+        it.dst16 = d.dst16 + dt0 * d_tok;
+        it.n = row0 | ((rows - 1) << 20);
+    }
+    return it;
+}
+
 __device__ __forceinline__ uint32_t desc_items(const Geo &g, const Desc &d)
 {
     if (g.mode >= kRelayoutHT2TH) return ((d.a >> 20) * g.hk + g.rows_per_item - 1) / g.rows_per_item;
@@ -343,23 +367,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             }
             const Desc d = a.desc[w0 + lo];
             const uint32_t cl = c - d.prefix;
-            Item it;
-            it.layers = a.layers;
-            if (!relayout) {
-                it.src16 = d.src16 + cl * kChunkUnits;
-                it.dst16 = d.dst16 + cl * kChunkUnits;
-                it.n = min(kChunkUnits, d.a - d.src16 - cl * kChunkUnits);
-            } else {
-                const uint32_t st0 = d.a & 1023u, dt0 = (d.a >> 10) & 1023u, ntok = d.a >> 20;
-                const uint32_t row0 = cl * g.rows_per_item;
-                const uint32_t rows = min(g.rows_per_item, ntok * g.hk - row0);
-                // fold the first token's slot into the bases (both layouts are linear in the slot)
-                const uint32_t s_tok = (g.mode == kRelayoutHT2TH) ? g.du : g.hk * g.du;
-                const uint32_t d_tok = (g.mode == kRelayoutHT2TH) ? g.hk * g.du : g.du;
-                it.src16 = d.src16 + st0 * s_tok;
-                it.dst16 = d.dst16 + dt0 * d_tok;
-                it.n = row0 | ((rows - 1) << 20);
-            }
+            const Item it = make_item(g, d, cl, a.layers);
             a.items[c] = it;
         }
         __syncthreads();
@@ -486,19 +494,66 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
     move_unit(g, a, it, blockIdx.y, (piece % kParts) * T + threadIdx.x);
 }
 
-// Persistent form: a fixed grid walks the same (slab, piece) space in the same order.
-template <int T>
-__global__ __launch_bounds__(T) void kvd_pull_loop_kernel(Geo g, PullArgs a)
+// Persistent form, kept for comparison: a fixed grid of 1024-lane workgroups stages the coalesced
+// descriptors in LDS (a window of kLdsDescs at a time), every wave finds the descriptor of its
+// 4 KiB work item by a search over the staged prefixes and moves it with four loads and four
+// stores per lane, for one slab after the other.  On MI355X this is 15-20 % of HBM peak slower
+// than kvd_pull_kernel: waves of a persistent grid drift apart and the store stream loses its order.
+constexpr uint32_t kLdsDescs = 2048;
+
+__global__ __launch_bounds__(1024) void kvd_pull_persistent_kernel(Geo g, PullArgs a, const Desc *desc,
+                                                                  uint32_t layers)
 {
-    constexpr uint32_t kParts = kChunkUnits / T;
+    __shared__ Desc s_desc[kLdsDescs];
     const Header h = *a.hdr;
-    const uint64_t per_slab = (((uint64_t)h.n_items * kParts + 7) >> 3) << 3, total = per_slab * a.slabs;
-    for (uint64_t w = blockIdx.x; w < total; w += gridDim.x) {
-        const uint32_t y = (uint32_t)(w / per_slab), x = (uint32_t)(w - y * per_slab);
-        uint32_t piece;
-        if (!pick_piece<T>(h, x, &piece)) continue;
-        const Item it = a.items[piece / kParts];
-        move_unit(g, a, it, y, (piece % kParts) * T + threadIdx.x);
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1);
+    const uint32_t W = blockIdx.x * (blockDim.x / kWave) + tid / kWave, NW = gridDim.x * (blockDim.x / kWave);
+    for (uint32_t w0 = 0; w0 < h.n_desc; w0 += kLdsDescs) {
+        const uint32_t nw = min(kLdsDescs, h.n_desc - w0);
+        __syncthreads();
+        for (uint32_t i = tid; i < nw; i += blockDim.x) s_desc[i] = desc[w0 + i];
+        __syncthreads();
+        const uint32_t item_lo = s_desc[0].prefix;
+        const uint32_t nc = ((w0 + nw == h.n_desc) ? h.n_items : desc[w0 + nw].prefix) - item_lo;
+        // rounds 0..full-1: wave W takes item r*NW + W through every slab; last round: the
+        // remaining items are spread over all waves by also splitting the slabs
+        const uint32_t full = nc / NW, rem = nc - full * NW;
+        for (uint32_t r = 0; r <= full; ++r) {
+            uint32_t c, y0 = 0, ystep = 1;
+            if (r < full) {
+                c = r * NW + W;
+            } else {
+                if (rem == 0) break;
+                const uint32_t phases = min(NW / rem, a.slabs);
+                if (W >= rem * phases) break;
+                y0 = W / rem;
+                c = full * NW + (W - y0 * rem);
+                ystep = phases;
+            }
+            c += item_lo;
+            uint32_t lo = 0, hi = nw;  // largest i with prefix[i] <= c
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s_desc[mid].prefix <= c) lo = mid; else hi = mid;
+            }
+            const Desc d = s_desc[lo];
+            const Item it = make_item(g, d, c - d.prefix, layers);
+            uint32_t s16[4], d16[4];
+            bool ok[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) ok[k] = unit_offsets(g, it, 0, k * kWave + lane, &s16[k], &d16[k]);
+            for (uint32_t y = y0; y < a.slabs; y += ystep) {
+                const unsigned char *sp = src_slab(g, a, it, y);
+                unsigned char *dp = dst_slab(g, a, it, y);
+                u32x4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (ok[k]) v[k] = __builtin_nontemporal_load((const u32x4 *)(sp + (size_t)s16[k] * kUnitBytes));
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (ok[k]) stream_store(v[k], (u32x4 *)(dp + (size_t)d16[k] * kUnitBytes));
+            }
+        }
     }
 }
 
@@ -975,8 +1030,12 @@ int kvd_pull(kvd_plan_t *p, void *stream)
     a.slabs = p->max_layers << p->geo.kv_shift;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
-        const uint32_t grid = (uint32_t)p->num_cus * (2048 / T);
-        hipLaunchKernelGGL(kvd_pull_loop_kernel<T>, dim3(grid), dim3(T), 0, (hipStream_t)stream, p->geo, a);
+        for (const ReqHost &r : p->reqs)
+            if (r.layer_begin != p->reqs[0].layer_begin || r.layer_end != p->reqs[0].layer_end)
+                return fail(KVD_ERR_MISMATCH, "the persistent form needs one layer range for the whole plan");
+        const uint32_t layers = p->reqs[0].layer_begin | ((p->reqs[0].layer_end - p->reqs[0].layer_begin) << 16);
+        hipLaunchKernelGGL(kvd_pull_persistent_kernel, dim3((uint32_t)p->num_cus * 2), dim3(1024), 0,
+                           (hipStream_t)stream, p->geo, a, p->desc_dev, layers);
     } else {
         // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
         const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;

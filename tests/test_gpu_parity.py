@@ -239,9 +239,14 @@ def test_requests_with_different_layers_do_not_merge():
 
 
 @pytest.mark.parametrize("w", [wl.config2(num_layers=2, pool_blocks=1024, tokens=3000),
-                               wl.config5(num_layers=2, src_pool_blocks=256, tokens=1500)], ids=lambda w: w.name)
+                               wl.config5(num_layers=2, src_pool_blocks=256, tokens=1500),
+                               wl.config4(num_layers=3, pool_blocks=8192, tokens=48000),   # 3000 descriptors: two LDS windows
+                               wl.config3(num_layers=2, num_requests=16, median=256.0, hi=2048)], ids=lambda w: w.name)
 def test_persistent_grid_form_gives_the_same_bytes(w):
-    G.run_and_compare(w, host_src(w), flags=kvd.KVD_PLAN_PERSISTENT).close()
+    x = G.run_and_compare(w, host_src(w), flags=kvd.KVD_PLAN_PERSISTENT)
+    if w.name.startswith("cfg4"):
+        assert x.plan.stats(x.stream.cuda_stream)["num_descriptors"] == 3000
+    x.close()
 
 
 def test_many_transactions_and_one_long_run():
