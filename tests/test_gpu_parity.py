@@ -484,6 +484,71 @@ def test_slab_larger_than_4_gib():
     torch.cuda.empty_cache()
 
 
+def _random_case(seed):
+    """A seeded random small transfer: geometry, layouts, block sizes, several requests with their own
+    layer ranges, plan flags."""
+    rng = np.random.default_rng(5000 + seed)
+    elem = int(rng.choice([1, 2, 2, 2, 4, 8]))
+    row_units = int(rng.choice([1, 2, 3, 4, 8, 12, 16]))            # 16-byte units per (token, head) row
+    head_dim = row_units * 16 // elem
+    hk = int(rng.choice([1, 1, 2, 3, 4, 8]))
+    layers = int(rng.integers(1, 5))
+    tb_s = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+    ratio = int(rng.choice([1, 1, 1, 2, 4]))
+    tb_d = tb_s * ratio if rng.random() < 0.5 else max(1, tb_s // ratio)
+    lay_s, lay_d = (str(rng.choice([wl.BHTD, wl.BTHD])) for _ in range(2))
+    adj_s, adj_d = (bool(rng.random() < 0.3) for _ in range(2))
+    n_req = int(rng.integers(1, 5))
+    lens = [int(rng.integers(1, 400)) for _ in range(n_req)]
+    need_s = sum(wl.blocks_for(t, tb_s) for t in lens)
+    need_d = sum(wl.blocks_for(t, tb_d) for t in lens)
+    gs = wl.PoolGeometry(layers, need_s + int(rng.integers(1, 40)), tb_s, hk, head_dim, elem, lay_s, adj_s)
+    gd = wl.PoolGeometry(layers, need_d + int(rng.integers(1, 40)), tb_d, hk, head_dim, elem, lay_d, adj_d)
+    free_s, free_d = np.ones(gs.num_blocks, bool), np.ones(gd.num_blocks, bool)
+    reqs, ranges = [], []
+    uniform = rng.random() < 0.6
+    for t in lens:
+        reqs.append(wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, tb_s), 5),
+                               wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, tb_d), 5)))
+        l0 = 0 if uniform else int(rng.integers(0, layers))
+        ranges.append((l0, layers if uniform else int(rng.integers(l0 + 1, layers + 1))))
+    flags = 0
+    if rng.random() < 0.2:
+        flags |= kvd.KVD_PLAN_NO_COALESCE
+    if uniform and rng.random() < 0.25:
+        flags |= kvd.KVD_PLAN_PERSISTENT
+    if tb_s == tb_d and rng.random() < 0.25:
+        flags |= kvd.KVD_PLAN_WHOLE_BLOCKS
+    return gs, gd, reqs, ranges, flags, bool(uniform and n_req > 1 and rng.random() < 0.5)
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_small_transfers(seed):
+    gs, gd, reqs, ranges, flags, batch = _random_case(seed)
+    say(f"seed {seed}: {gs} -> {gd}, lens {[r.seq_len for r in reqs]}, layers {ranges}, flags {flags}, batch {batch}")
+    rng = np.random.default_rng(seed)
+    src_host = rng.integers(0, 256, size=gs.total_bytes, dtype=np.uint8)
+    want = wl.host_pool_sentinel(gd)
+    src, dst = G.device_pool_from_host(src_host), G.device_pool_from_host(want.copy())
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst.data_ptr(), gd), len(reqs),
+                    sum(max(len(r.src_table), len(r.dst_table)) for r in reqs), flags)
+    whole = bool(flags & kvd.KVD_PLAN_WHOLE_BLOCKS)
+    if batch:
+        plan.build_descriptors_batch([r.src_table for r in reqs], [r.dst_table for r in reqs],
+                                     [r.seq_len for r in reqs], ranges[0][0], ranges[0][1])
+    for r, (l0, l1) in zip(reqs, ranges):
+        if not batch:
+            plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1)
+        t = wl.blocks_for(r.seq_len, gs.block_tokens) * gs.block_tokens if whole else r.seq_len
+        w1 = wl.Workload("one", gs, gd, [wl.Request(t, r.src_table, r.dst_table)], "bf16", 0, l0, l1)
+        tl.oracle_pull_workload(w1, src_host, want)
+    plan.pull()
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, f"random case {seed}")
+    G.assert_bytes_equal(src.cpu().numpy(), src_host, f"random case {seed}: source changed")
+    plan.close()
+
+
 # ------------------------------------------------------------------ full-size configurations
 
 def _check_full(w, sample_layers):
