@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the reported GPU baselines")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="also time the transfer issued one layer per launch, alone and next to GEMMs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
@@ -194,7 +196,7 @@ def main() -> int:
             del sb, rb
         # push-mode-like use (section 4.3): one layer per launch, as a prefill worker would issue them,
         # alone and next to a compute-bound kernel on another stream
-        if len(w.requests) == 1 and not stats["relayout"]:
+        if args.per_layer and len(w.requests) == 1 and not stats["relayout"]:
             r = w.requests[0]
             layers = range(w.layer_begin, w.layer_end)
 
