@@ -153,6 +153,23 @@ def test_valid_build_needs_a_gpu_and_says_so():
     expect(kvd.KVD_ERR_HIP, plan.build_descriptors, ok, ok, 128, 0, 2)
 
 
+def test_product_path_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing in the package or the header may name it, and
+    the oracle may not name the package's library either."""
+    pkg = os.path.join(ROOT, "paper_2501_14743_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "workloads.py" and "import" not in \
+                    [ln for ln in text.splitlines() if "oracle" in ln.lower()][0], f
+    assert "oracle" not in open(os.path.join(ROOT, "include", "kvd.h")).read().lower()
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "libkvd.so" not in text and "paper_2501_14743_amd" not in text, f
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(kvd, "_lib", None)
     monkeypatch.setattr(kvd, "LIB_PATH", "/nonexistent/libkvd.so")
