@@ -656,19 +656,30 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
     const uint64_t block_axis = ((uint64_t)(d.num_blocks - 1) * d.stride_block + tile) * e;
     if (block_axis >= (1ull << 36))
         return fail(KVD_ERR_RANGE, "block axis of one slab spans more than 64 GiB");
-    *extent_out = ((uint64_t)(d.num_layers - 1) * d.stride_layer + (uint64_t)d.stride_kv) * e + block_axis;
+    // the layer, K/V and block axes must nest without overlap, in whatever order the strides put them
+    struct Axis { uint64_t n, stride; } ax[3] = {{d.num_layers, (uint64_t)d.stride_layer},
+                                                 {2, (uint64_t)d.stride_kv},
+                                                 {d.num_blocks, (uint64_t)d.stride_block}};
+    std::sort(ax, ax + 3, [](const Axis &x, const Axis &y) { return x.stride < y.stride; });
+    uint64_t extent = tile;
+    for (const Axis &x : ax) {
+        if (x.n > 1 && x.stride < extent)
+            return fail(KVD_ERR_INVALID, "layer, K/V and block axes overlap (a stride of %llu elements is smaller than "
+                        "the %llu elements nested inside it)", (unsigned long long)x.stride, (unsigned long long)extent);
+        extent += (x.n - 1) * x.stride;
+    }
+    *extent_out = extent * e;
     return KVD_OK;
 }
 
 uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
-// Sizes of one request per (layer, kv): read transactions, the leading whole-block ones, and
-// the work items they need before any merging (an upper bound of the number after merging).
-void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *n_single, uint32_t *items)
+// Sizes of one request per (layer, kv): read transactions, and the work items they need before
+// any merging (an upper bound of the number after merging).
+void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *items)
 {
     const uint32_t pieces = ceil_div(seq_len, g.piece_tokens);
     const uint32_t whole = seq_len / g.piece_tokens, tail = seq_len % g.piece_tokens;
-    *n_single = 0;
     if (g.mode >= kRelayoutHT2TH) {
         *n_txn = pieces;
         *items = whole * ceil_div(g.piece_tokens * g.hk, g.rows_per_item) +
@@ -682,7 +693,6 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *n_
         *items = g.hk * (whole * ceil_div(g.piece_tokens * g.du, kChunkUnits) +
                          (tail ? ceil_div(tail * g.du, kChunkUnits) : 0));
     } else {
-        *n_single = whole;
         *n_txn = whole + (tail ? g.hk : 0);
         *items = whole * ceil_div(g.piece_tokens * g.hk * g.du, kChunkUnits) +
                  (tail ? g.hk * ceil_div(tail * g.du, kChunkUnits) : 0);
@@ -901,8 +911,8 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         for (uint32_t i = 0; i < need_dst; ++i)
             if (dt[i] < 0 || (uint32_t)dt[i] >= p->dst.num_blocks)
                 return fail(KVD_ERR_RANGE, "request %u: destination block id %d at entry %u outside [0, %u)", k, dt[i], i, p->dst.num_blocks);
-        uint32_t n_txn = 0, n_single = 0, items = 0;
-        request_sizes(g, seq_len, &n_txn, &n_single, &items);
+        uint32_t n_txn = 0, items = 0;
+        request_sizes(g, seq_len, &n_txn, &items);
         add_src += need_src;
         add_dst += need_dst;
         add_txn += n_txn;
@@ -974,8 +984,8 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         uint32_t batch_txn = 0, batch_items = 0;
         for (uint32_t i = 0; i < nb; ++i) {
             const ReqHost &r = p->reqs[b0 + i];
-            uint32_t n_txn = 0, n_single = 0, items = 0;
-            request_sizes(g, r.seq_len, &n_txn, &n_single, &items);
+            uint32_t n_txn = 0, items = 0;
+            request_sizes(g, r.seq_len, &n_txn, &items);
             p->reqs_pinned[b0 + i] = ReqDev{r.table_off_src, r.table_off_dst, r.seq_len, batch_txn};
             batch_txn += n_txn;
             batch_items += items;

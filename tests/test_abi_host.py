@@ -59,6 +59,11 @@ def test_pool_create_rejects_bad_metadata():
     expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(elem_bytes=3))
     expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, g, stride_block=g.tile_elems - 8)
     expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, geom(block_tokens=2048))
+    # axes that overlap: V of a block on top of the next block's K; layers closer than one layer's extent
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, g, g.stride_layer, g.tile_elems, g.tile_elems)
+    expect(kvd.KVD_ERR_INVALID, kvd.Pool, FAKE_SRC, g, g.stride_kv, g.stride_kv, g.stride_block)
+    # any nesting order of the three axes is fine: blocks outermost, then layers, then K/V
+    kvd.Pool(FAKE_SRC, g, 2 * g.tile_elems, g.tile_elems, 2 * g.num_layers * g.tile_elems).close()
     expect(kvd.KVD_ERR_INVALID, kvd.kvd_pool_create, FAKE_SRC, 2, 64, 16, 4, 64, 2, 7, 1 << 20, 1 << 19, 4096)
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8))
     p = kvd.Pool(FAKE_SRC, g)

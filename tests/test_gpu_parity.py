@@ -269,32 +269,46 @@ def test_many_transactions_and_one_long_run():
     x.close()
 
 
-def test_padded_block_stride_and_block_major_pool():
-    # blocks padded to 1.5 tiles, K and V of a block next to each other, layers outermost
-    g = small_geom(num_layers=2, num_blocks=32)
+def _strides(kind, g):
     tile = g.tile_elems
-    stride_block, stride_kv = 3 * tile, tile + tile // 2
-    stride_layer = g.num_blocks * stride_block
-    total = 2 * stride_layer * 2
+    if kind == "padded":          # layers outermost, blocks padded to 3 tiles, V half a tile behind K
+        sb, skv = 3 * tile, tile + tile // 2
+        return g.num_blocks * sb, skv, sb
+    if kind == "block-major":     # [block][layer][kv]: every block holds all its layers
+        return 2 * tile, tile, 2 * g.num_layers * tile
+    if kind == "kv-outermost":    # [kv][layer][block]
+        return g.num_blocks * tile, g.num_layers * g.num_blocks * tile, tile
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind_src,kind_dst", [("padded", "padded"), ("block-major", "block-major"),
+                                               ("kv-outermost", "block-major"), ("block-major", "padded")])
+def test_pools_described_only_by_their_strides(kind_src, kind_dst):
+    g = small_geom(num_layers=2, num_blocks=32)
     rng = np.random.default_rng(8)
-    src_host = wl.normal_bits(rng, total // 2, "bf16").view(np.uint8)
-    want = np.full(total // 2, wl.SENTINEL16, np.uint16).view(np.uint8)
-    st, dt = rng.permutation(32)[:7].astype(np.int32), rng.permutation(32)[:7].astype(np.int32)
     from oracle import kvd_oracle as orc
 
-    def tensors(buf):
-        return [orc.Tensor(buf, layer * stride_layer * 2, [orc.KV, orc.B, orc.H, orc.L, orc.D],
-                           [2, 32, 4, 16, 64], [stride_kv, stride_block, 16 * 64, 64, 1], 2) for layer in range(2)]
-    orc.pull(tensors(src_host), tensors(want), 0, 2, st, dt, 100)
+    def tensors(buf, strides):
+        sl, skv, sb = strides
+        return [orc.Tensor(buf, layer * sl * 2, [orc.KV, orc.B, orc.H, orc.L, orc.D],
+                           [2, 32, 4, 16, 64], [skv, sb, 16 * 64, 64, 1], 2) for layer in range(2)]
+
+    def extent(strides):
+        sl, skv, sb = strides
+        return (sl + skv + 31 * sb + g.tile_elems) * 2
+
+    ss, ds = _strides(kind_src, g), _strides(kind_dst, g)
+    src_host = wl.normal_bits(rng, extent(ss) // 2, "bf16").view(np.uint8)
+    want = np.full(extent(ds) // 2, wl.SENTINEL16, np.uint16).view(np.uint8)
+    st, dt = rng.permutation(32)[:7].astype(np.int32), rng.permutation(32)[:7].astype(np.int32)
+    orc.pull(tensors(src_host, ss), tensors(want, ds), 0, 2, st, dt, 100)
     src, dst = G.device_pool_from_host(src_host), G.device_pool_from_host(want.copy())
     dst.view(torch.int16).fill_(wl.SENTINEL16)
-    sp = kvd.Pool(src.data_ptr(), g, stride_layer, stride_kv, stride_block)
-    dp = kvd.Pool(dst.data_ptr(), g, stride_layer, stride_kv, stride_block)
-    plan = kvd.Plan(sp, dp, 1, 8)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), g, *ss), kvd.Pool(dst.data_ptr(), g, *ds), 1, 8)
     plan.build_descriptors(st, dt, 100, 0, 2)
     plan.pull()
     torch.cuda.synchronize()
-    G.assert_bytes_equal(dst.cpu().numpy(), want, "padded strides")
+    G.assert_bytes_equal(dst.cpu().numpy(), want, f"{kind_src} -> {kind_dst}")
     plan.close()
 
 
