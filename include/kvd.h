@@ -194,9 +194,12 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
  * blocking; section 4.3: all layers in a single shot).  Every read is cut into work items of at
  * most 4 KiB and each (work item, layer, K/V) is moved by its own small workgroup, 16 bytes per
- * lane.  May be called repeatedly; a plan with no requests is a no-op.  Completion (section 4.1, Complete()) is the caller's
- * synchronisation on `stream`.
- * Errors: KVD_ERR_INVALID, KVD_ERR_HIP.
+ * lane.  When the plan's transactions are short (fewer than four work items each, as for lone
+ * 4 KiB blocks) the first pull after an append is preceded by one small launch that groups the work
+ * items by destination region.  May be called repeatedly; a plan with no requests is a no-op.
+ * Completion (section 4.1, Complete()) is the caller's synchronisation on `stream`.
+ * Errors: KVD_ERR_INVALID, KVD_ERR_HIP, KVD_ERR_MISMATCH (KVD_PLAN_PERSISTENT with several layer
+ * ranges in one plan).
  */
 int kvd_pull(kvd_plan_t *plan, void *stream);
 

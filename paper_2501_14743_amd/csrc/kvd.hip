@@ -494,6 +494,61 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
     move_unit(g, a, it, blockIdx.y, (piece % kParts) * T + threadIdx.x);
 }
 
+// Order of the work items for plans made of short, scattered descriptors (fewer than four work
+// items each): items are grouped by the region of the destination slab they write to (buckets of
+// 2^shift units, at least 2 MiB), regions in address order.  Measured on MI355X: 80 layers of
+// 2048 lone 4 KiB blocks go from 69 % to 74 % of HBM peak; buckets as coarse as 2 MiB give the
+// whole gain, the order inside a bucket does not matter.  Plans with long descriptors keep the
+// queue order (grouping measured slower there).  One workgroup; a counting sort with the bucket
+// counters in LDS.
+constexpr uint32_t kOrderBuckets = 4096;
+
+__global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *items, Item *ordered, const Header *hdr,
+                                                                   uint32_t shift)
+{
+    __shared__ uint32_t s_count[kOrderBuckets];
+    __shared__ uint32_t s_wave[kBuildThreads / kWave];
+    const Header h = *hdr;
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    if (h.n_items >= 4 * h.n_desc) {  // long descriptors: keep the queue order
+        for (uint32_t i = tid; i < h.n_items; i += kBuildThreads) ordered[i] = items[i];
+        return;
+    }
+    for (uint32_t b = tid; b < kOrderBuckets; b += kBuildThreads) s_count[b] = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < h.n_items; i += kBuildThreads)
+        atomicAdd(&s_count[min(items[i].dst16 >> shift, kOrderBuckets - 1)], 1u);
+    __syncthreads();
+    // exclusive scan of the bucket counts: four consecutive buckets per lane
+    constexpr uint32_t kPer = kOrderBuckets / kBuildThreads;
+    uint32_t c[kPer], sum = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+        c[k] = s_count[tid * kPer + k];
+        sum += c[k];
+    }
+    uint32_t incl = sum;
+#pragma unroll
+    for (uint32_t o = 1; o < kWave; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t base = incl - sum;
+    for (uint32_t w = 0; w < wave; ++w) base += s_wave[w];
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+        s_count[tid * kPer + k] = base;
+        base += c[k];
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < h.n_items; i += kBuildThreads) {
+        const Item it = items[i];
+        ordered[atomicAdd(&s_count[min(it.dst16 >> shift, kOrderBuckets - 1)], 1u)] = it;
+    }
+}
+
 // Persistent form, kept for comparison: a fixed grid of 1024-lane workgroups stages the coalesced
 // descriptors in LDS (a window of kLdsDescs at a time), every wave finds the descriptor of its
 // 4 KiB work item by a search over the staged prefixes and moves it with four loads and four
@@ -621,6 +676,9 @@ struct kvd_plan {
     ReqDev *reqs_pinned, *reqs_pinned_dev;  // one entry per request, same kind of memory
     Desc *desc_dev;
     Item *items_dev;
+    Item *ordered_dev;     // items grouped by destination region (plans of short descriptors)
+    bool order_stale;      // requests were appended since ordered_dev was last written
+    uint32_t order_shift;  // log2 of the region size in 16-byte units
     Header *hdr_dev;
     hipEvent_t build_done;
     bool build_pending;
@@ -715,6 +773,7 @@ int ensure_allocated(kvd_plan *p)
     KVD_HIP(hipHostGetDevicePointer((void **)&p->reqs_pinned_dev, p->reqs_pinned, 0));
     KVD_HIP(hipMalloc((void **)&p->desc_dev, (size_t)p->max_txns * sizeof(Desc)));
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
+    KVD_HIP(hipMalloc((void **)&p->ordered_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
     KVD_HIP(hipEventCreateWithFlags(&p->build_done, hipEventDisableTiming));
     p->allocated = true;
@@ -730,6 +789,7 @@ void release_plan(kvd_plan *p)
         (void)hipHostFree(p->reqs_pinned);
         (void)hipFree(p->desc_dev);
         (void)hipFree(p->items_dev);
+        (void)hipFree(p->ordered_dev);
         (void)hipFree(p->hdr_dev);
         (void)hipEventDestroy(p->build_done);
     }
@@ -853,6 +913,13 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
         delete p;
         return fail(KVD_ERR_CAPACITY, "plan capacity too large");
     }
+    // destination regions for kvd_order_kernel: 2 MiB, or wider if the slab's block axis would
+    // need more buckets than the kernel keeps
+    const uint64_t dst_span16 = ((uint64_t)(d.num_blocks - 1) * d.stride_block +
+                                 (uint64_t)d.block_tokens * d.num_kv_heads * d.head_dim) * e / kUnitBytes;
+    p->order_shift = 17;
+    while ((dst_span16 >> p->order_shift) >= kOrderBuckets) ++p->order_shift;
+    p->order_stale = true;
     p->dst_used.assign(d.num_blocks, 0);
     p->reqs.reserve(max_requests);
     p->allocated = false;
@@ -1014,6 +1081,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
             return fail(KVD_ERR_HIP, "launch of the build kernel failed (plan was reset): %s", hipGetErrorString(launch));
         }
         p->build_pending = true;
+        p->order_stale = true;
         p->txns_total += batch_txn;
         p->item_bound += batch_items;
     }
@@ -1047,6 +1115,17 @@ int kvd_pull(kvd_plan_t *p, void *stream)
         hipLaunchKernelGGL(kvd_pull_persistent_kernel, dim3((uint32_t)p->num_cus * 2), dim3(1024), 0,
                            (hipStream_t)stream, p->geo, a, p->desc_dev, layers);
     } else {
+        // transactions shorter than four work items on average (known on the host before merging):
+        // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination region
+        if (p->item_bound < 4 * p->txns_total) {
+            if (p->order_stale) {
+                hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
+                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift);
+                KVD_HIP(hipGetLastError());
+                p->order_stale = false;
+            }
+            a.items = p->ordered_dev;
+        }
         // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
         const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;
         if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
