@@ -46,12 +46,15 @@ class GpuTransfer:
         self.dst_pool = kvd.Pool(dst.data_ptr(), w.dst)
         max_blocks = sum(max(len(r.src_table), len(r.dst_table)) for r in w.requests) + 1
         self.plan = kvd.Plan(self.src_pool, self.dst_pool, max(1, len(w.requests)), max_blocks, flags)
+        self.after_torch()
+
+    def after_torch(self):
+        """Order this object's stream after what torch has queued on its current stream (pool fills)."""
+        self.stream.wait_stream(torch.cuda.current_stream())
 
     def build(self, batch: bool = False):
         """Append every request of the workload: one call each, or one batched call."""
         w = self.w
-        # pools are filled by torch on its current stream; order this stream after that work
-        self.stream.wait_stream(torch.cuda.current_stream())
         if batch:
             self.plan.build_descriptors_batch([r.src_table for r in w.requests], [r.dst_table for r in w.requests],
                                               [r.seq_len for r in w.requests], w.layer_begin, w.layer_end,

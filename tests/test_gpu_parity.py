@@ -326,6 +326,7 @@ def test_plan_reuse_reset_repeat_and_round_trip():
     x.plan.reset()
     assert x.plan.stats(x.stream.cuda_stream)["num_requests"] == 0
     mid.view(torch.int16).fill_(wl.SENTINEL16)
+    x.after_torch()
     r = w.requests[0]
     w2 = wl.Workload("again", w.src, w.dst, [wl.Request(300, r.src_table[::-1].copy(), r.dst_table[::-1].copy())], "bf16", 0)
     x.w = w2
