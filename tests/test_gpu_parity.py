@@ -249,6 +249,36 @@ def test_persistent_grid_form_gives_the_same_bytes(w):
     x.close()
 
 
+def test_region_ordering_of_short_scattered_transactions():
+    """Enough lone small blocks for the pull to group its work items by destination region first."""
+    g = wl.PoolGeometry(16, 65536, 16, 1, 8, 2, wl.BHTD)        # 256-byte blocks, 16 MiB slabs
+    rng = np.random.default_rng(41)
+    n = 4096
+    st, dt = wl.scattered_table(rng, g.num_blocks, n), wl.scattered_table(rng, g.num_blocks, n)
+    big = wl.Request(n * 16 - 5, st, dt)
+    extra = wl.Request(40, np.array([5, 9, 11], np.int32), np.setdiff1d(np.arange(g.num_blocks), dt)[:3].astype(np.int32))
+    w = wl.Workload("ordered", g, g, [big, extra], "bf16", 41)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst)
+    sh = x.stream.cuda_stream
+    x.plan.build_descriptors(big.src_table, big.dst_table, big.seq_len, 0, g.num_layers, sh)
+    x.pull()
+    x.stream.synchronize()
+    stt = x.plan.stats(sh)
+    assert stt["num_work_items"] == n == stt["num_descriptors"]
+    want = wl.host_pool_sentinel(g)
+    tl.oracle_pull_workload(wl.Workload("big", g, g, [big], "bf16", 0), src_host, want)
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "region-ordered pull")
+    # appending to the plan re-orders on the next pull; a second pull reuses the order
+    x.plan.build_descriptors(extra.src_table, extra.dst_table, extra.seq_len, 0, g.num_layers, sh)
+    x.pull(); x.pull()
+    x.stream.synchronize()
+    tl.oracle_pull_workload(wl.Workload("extra", g, g, [extra], "bf16", 0), src_host, want)
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "after appending")
+    x.close()
+
+
 def test_many_transactions_and_one_long_run():
     # 16-byte rows, one head: 10000 lone blocks -> several passes of the coalescing workgroup
     g = wl.PoolGeometry(2, 20000, 16, 1, 8, 2, wl.BHTD)
