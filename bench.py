@@ -31,7 +31,7 @@ def log(msg: str) -> None:
 
 def cpu_baseline(cfg_no: int, budget_s: float = 12.0) -> dict:
     """Time the oracle (as it stands, one thread) on a bounded sample: layer 0 of the same
-    workload, repeated until about `budget_s` seconds of CPU work have been spent."""
+    workload, repeated (at most 256 times) until about `budget_s` seconds of CPU work have been spent."""
     import numpy as np
     import kvd_testlib as tl
     from paper_2501_14743_amd import workloads as wl
@@ -48,7 +48,7 @@ def cpu_baseline(cfg_no: int, budget_s: float = 12.0) -> dict:
     t0 = time.perf_counter()
     tl.oracle_pull_workload(w, src, dst)
     first = time.perf_counter() - t0
-    reps = max(1, min(32, int(budget_s / max(first, 1e-3))))
+    reps = max(1, min(256, int(budget_s / max(first, 1e-3))))
     t0 = time.perf_counter()
     for _ in range(reps):
         tl.oracle_pull_workload(w, src, dst)

@@ -3,6 +3,7 @@ the header declares, and rejects bad arguments before anything is launched."""
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -156,6 +157,51 @@ def test_valid_build_needs_a_gpu_and_says_so():
     assert "hip" in msg.lower()
     # the failed call left no trace: the same destination blocks can be used again
     expect(kvd.KVD_ERR_HIP, plan.build_descriptors, ok, ok, 128, 0, 2)
+
+
+C_PROGRAM = r"""
+#include <stdio.h>
+#include <string.h>
+#include "kvd.h"
+int main(void)
+{
+    kvd_pool_desc_t d;
+    kvd_pool_t *src = NULL, *dst = NULL;
+    kvd_plan_t *plan = NULL;
+    kvd_stats_t st;
+    int32_t tbl[4] = {0, 1, 2, 99};
+    memset(&d, 0, sizeof d);
+    if (kvd_pool_create(&d, &src) != KVD_ERR_INVALID || kvd_last_error()[0] == 0) return 1;
+    d.base = (void *)0x100000000ull; d.num_layers = 2; d.num_blocks = 8; d.block_tokens = 16;
+    d.num_kv_heads = 2; d.head_dim = 64; d.elem_bytes = 2; d.layout = KVD_LAYOUT_BHTD;
+    d.stride_block = 16 * 2 * 64; d.stride_kv = 8 * d.stride_block; d.stride_layer = 2 * d.stride_kv;
+    if (kvd_pool_create(&d, &src) != KVD_OK) return 2;
+    d.base = (void *)0x200000000ull;
+    if (kvd_pool_create(&d, &dst) != KVD_OK) return 3;
+    if (kvd_plan_create(src, dst, 4, 16, KVD_PLAN_NO_COALESCE, &plan) != KVD_OK) return 4;
+    kvd_free(src); kvd_free(dst);                       /* the plan keeps its own copy of the metadata */
+    if (kvd_build_descriptors(plan, tbl, 4, tbl, 4, 64, 0, 2, NULL) != KVD_ERR_RANGE) return 5;
+    if (kvd_build_descriptors(plan, tbl, 4, tbl, 4, 0, 0, 2, NULL) != KVD_OK) return 6;
+    if (kvd_pull(plan, NULL) != KVD_OK) return 7;       /* empty plan: nothing to launch */
+    if (kvd_plan_stats(plan, NULL, &st) != KVD_OK || st.num_requests != 0) return 8;
+    if (kvd_plan_reset(plan) != KVD_OK) return 9;
+    kvd_free(plan); kvd_free(NULL);
+    printf("ok %s\n", kvd_last_error());
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_usable_from_c(tmp_path):
+    src, exe = tmp_path / "abi.c", tmp_path / "abi"
+    src.write_text(C_PROGRAM)
+    pkg = os.path.join(ROOT, "paper_2501_14743_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe), "-L", pkg, "-lkvd", f"-Wl,-rpath,{pkg}",
+                           "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    assert out.stdout.startswith("ok")
 
 
 def test_product_path_never_touches_the_oracle():
