@@ -11,8 +11,11 @@
 //                      hardware dispatcher hands the work items out in table order, which
 //                      keeps the traffic an orderly sweep; measured on MI355X this beats a
 //                      persistent grid that walks LDS-staged descriptors.
+//   kvd_order_kernel   for plans of short scattered descriptors: groups the work items by
+//                      destination region before the first pull.
 //   kvd_pull_persistent_kernel  persistent grid with the descriptors staged in LDS (kept for
 //                      comparison).
+//   kvd_stage_kernel   gather into / scatter out of a staging buffer (message-style baseline).
 //   kvd_copy_kernel    plain streaming copy (counter calibration / practical ceiling).
 //
 // Descriptors and work items are relative to the (layer 0, K) slab; the pull kernel adds the
