@@ -6,7 +6,8 @@ Both runs must be `bench.py ... --copy-calibration`, which also launches the pla
 1 GiB.  FETCH_SIZE / WRITE_SIZE are reported per dispatch in nominal KiB; each is scaled by
 (1 GiB in KiB) / (what the same counter reads for the plain 1 GiB copy), so the result does not
 depend on the counter's unit.  Writes `hbm_traffic.json` next to this file; bench.py reports its
-`traffic_bytes_per_launch` only while the kernel source still has the recorded hash.
+`traffic_bytes_per_launch` only while the kernel source (comments and white space aside) still has the
+recorded hash.
 """
 from __future__ import annotations
 
@@ -14,6 +15,7 @@ import csv
 import hashlib
 import json
 import os
+import re
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
@@ -23,8 +25,14 @@ COPY_BYTES = 1 << 30
 
 
 def source_hash() -> str:
-    with open(SOURCE, "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()
+    """sha256 of the kernel source with comments and white space removed, so that only a change
+    of the code invalidates a recorded measurement."""
+    with open(SOURCE) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    text = re.sub(r"//[^\n]*", "", text)
+    text = re.sub(r"\s+", "", text)
+    return hashlib.sha256(text.encode()).hexdigest()
 
 
 def load_record(workload: str):
