@@ -312,3 +312,40 @@ def test_config1_shapes():
     w = wl.config1()
     assert w.src.tile_elems * 2 == 8192 and len(w.requests[0].src_table) == 8
     assert orc.transfer_bytes(128, 2, 4, 64, 2) == 256 * 1024
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_oracle_equals_brute_force_on_random_tiny_geometries(seed):
+    """Random small shapes: inner orders, block-size ratios, K/V placement, element widths, layer ranges."""
+    rng = np.random.default_rng(900 + seed)
+    elem = int(rng.choice([1, 2, 4]))
+    hk, dd, layers = int(rng.integers(1, 4)), int(rng.choice([2, 4, 8])), int(rng.integers(1, 4))
+    tbs = int(rng.choice([1, 2, 4, 8]))
+    tbd = tbs * int(rng.choice([1, 2, 4])) if rng.random() < 0.5 else max(1, tbs // int(rng.choice([1, 2, 4])))
+    tokens = int(rng.integers(1, 40))
+    gs = wl.PoolGeometry(layers, wl.blocks_for(tokens, tbs) + 3, tbs, hk, dd, elem,
+                         str(rng.choice([wl.BHTD, wl.BTHD])), bool(rng.random() < 0.4))
+    gd = wl.PoolGeometry(layers, wl.blocks_for(tokens, tbd) + 3, tbd, hk, dd, elem,
+                         str(rng.choice([wl.BHTD, wl.BTHD])), bool(rng.random() < 0.4))
+    l0 = int(rng.integers(0, layers))
+    l1 = int(rng.integers(l0 + 1, layers + 1))
+    w = wl.Workload("rand", gs, gd, [wl.Request(tokens, wl.permutation_table(rng, gs.num_blocks, wl.blocks_for(tokens, tbs)),
+                                                wl.permutation_table(rng, gd.num_blocks, wl.blocks_for(tokens, tbd)))],
+                    "bf16", seed, l0, l1)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32}[elem]
+    src = rng.integers(0, 200, size=gs.total_elems).astype(dt)
+    dst_o = np.full(gd.total_elems, 0xA5, dtype=dt)
+    dst_b = dst_o.copy()
+    tl.oracle_pull_workload(w, src.view(np.uint8), dst_o.view(np.uint8))
+    count = tl.brute_force_pull(w, src, dst_b)
+    assert np.array_equal(dst_o, dst_b)
+    assert count.max() == 1 and int(count.sum()) == tokens * (l1 - l0) * 2 * hk * dd
+    # the transactions of every layer tensor tile the moved bytes exactly once on both sides
+    s_t, d_t = tl.oracle_tensors(gs, None)[l0], tl.oracle_tensors(gd, None)[l0]
+    q = orc.request_transactions(s_t, d_t, -1, w.requests[0].src_table, w.requests[0].dst_table, tokens)
+    assert q[:, 2].sum() == tokens * 2 * hk * dd * elem
+    for col in (0, 1):
+        o = np.argsort(q[:, col])
+        assert np.all(q[o, col][1:] >= (q[o, col] + q[o, 2])[:-1])  # no two ranges overlap
+    m = orc.coalesce(q)
+    assert m[:, 2].sum() == q[:, 2].sum() and len(m) <= len(q)
