@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the reported GPU baselines")
+    ap.add_argument("--no-slow-baselines", action="store_true",
+                    help="skip the staged and the per-block memcpy baselines (hundreds of thousands of launches)")
     ap.add_argument("--per-layer", action="store_true",
                     help="also time the transfer issued one layer per launch, alone and next to GEMMs")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -178,6 +180,12 @@ def main() -> int:
         extras["no_coalesce_pull_us"] = us
         extras["no_coalesce_descriptors"] = y.plan.stats(sh)["num_descriptors"]
         y.close()
+        # plans of short transactions: the same pull without grouping the work items by destination region
+        if stats["num_work_items"] < 4 * stats["num_transactions"]:
+            y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_QUEUE_ORDER, stream=stream)
+            y.build(batch)
+            extras["queue_order_pull_us"] = timed(lambda: y.plan.pull(sh), 10)
+            y.close()
         # the same work items walked by a persistent grid instead of one workgroup per item
         y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_PERSISTENT, stream=stream)
         y.build()
@@ -186,7 +194,7 @@ def main() -> int:
         # the buffer-based scheme: gather kernel -> copy -> host wait -> scatter kernel -> host wait, with a
         # staging buffer that holds two blocks (the paper's figure) and one that holds 64 MiB
         tile = w.src.tile_elems * w.src.elem_bytes
-        for label, nbytes in (("two_blocks", max(4096, 2 * tile)), ("64MiB", 64 << 20)):
+        for label, nbytes in (() if args.no_slow_baselines else (("two_blocks", max(4096, 2 * tile)), ("64MiB", 64 << 20))):
             sb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             rb = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             torch.cuda.synchronize()
@@ -232,7 +240,7 @@ def main() -> int:
             x.plan.reset()
             x.build(batch)
         # one hipMemcpyAsync per (layer, K/V, block)
-        if not stats["relayout"]:
+        if not stats["relayout"] and not args.no_slow_baselines:
             torch.cuda.synchronize()
             t = time.perf_counter()
             x.plan.pull_blockwise_memcpy(sh)

@@ -87,6 +87,8 @@ typedef struct kvd_plan kvd_plan_t;
 #define KVD_PLAN_WHOLE_BLOCKS 4u /* move every slot of a request's last block, not only the tokens below
                                    seq_len: the block-granular transfer of section 4.1 (needs equal
                                    block sizes, else KVD_ERR_MISMATCH)                              */
+#define KVD_PLAN_QUEUE_ORDER 8u  /* never group the work items by destination region: kvd_pull walks them
+                                   in queue order whatever the plan looks like (ablation)           */
 #define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a persistent grid that stages the coalesced descriptors
                                    in LDS and walks them wave by wave, instead of one small workgroup
                                    per work item (for comparison; slower; one layer range per plan) */

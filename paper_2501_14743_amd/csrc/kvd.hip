@@ -1121,7 +1121,8 @@ int kvd_pull(kvd_plan_t *p, void *stream)
         // transactions shorter than four work items on average (known on the host before merging):
         // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination
         // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
-        if (p->item_bound < 4 * p->txns_total && p->item_bound * a.slabs >= (1u << 17)) {
+        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
+            p->item_bound * a.slabs >= (1u << 17)) {
             if (p->order_stale) {
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
                                    p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift);

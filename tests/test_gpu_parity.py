@@ -270,6 +270,12 @@ def test_region_ordering_of_short_scattered_transactions():
     want = wl.host_pool_sentinel(g)
     tl.oracle_pull_workload(wl.Workload("big", g, g, [big], "bf16", 0), src_host, want)
     G.assert_bytes_equal(dst.cpu().numpy(), want, "region-ordered pull")
+    # the ablation flag keeps the queue order and moves the same bytes
+    dst2 = G.device_sentinel_pool(g)
+    wq = wl.Workload("queue-order", g, g, [big], "bf16", 41)
+    y = G.GpuTransfer(wq, src, dst2, flags=kvd.KVD_PLAN_QUEUE_ORDER).run()
+    G.assert_bytes_equal(dst2.cpu().numpy(), want, "queue-order pull")
+    y.close()
     # appending to the plan re-orders on the next pull; a second pull reuses the order
     x.plan.build_descriptors(extra.src_table, extra.dst_table, extra.seq_len, 0, g.num_layers, sh)
     x.pull(); x.pull()
