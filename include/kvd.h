@@ -95,7 +95,8 @@ typedef struct kvd_plan kvd_plan_t;
 
 /* A coalesced read transaction of the byte-copy path, relative to (layer 0, K): the copy for
  * (layer, kv) adds layer*stride_layer*elem_bytes + kv*stride_kv*elem_bytes of the respective
- * pool to both offsets. */
+ * pool to both offsets.  In plans whose K and V are adjacent on both sides (see kvd_plan_create)
+ * a transaction may span K and V and only the layer offset is added. */
 typedef struct {
     uint64_t src_offset; /* bytes from the source pool's base       */
     uint64_t dst_offset; /* bytes from the destination pool's base  */
