@@ -73,6 +73,9 @@ def main() -> int:
                     help="skip the staged and the per-block memcpy baselines (hundreds of thousands of launches)")
     ap.add_argument("--per-layer", action="store_true",
                     help="also time the transfer issued one layer per launch, alone and next to GEMMs")
+    ap.add_argument("--run-length-sweep", action="store_true",
+                    help="also time the pull of the same token count with block tables made of runs of exactly "
+                         "1, 2, 4, ... consecutive blocks (both sides, source only, destination only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
@@ -239,6 +242,32 @@ def main() -> int:
             del ma, mb
             x.plan.reset()
             x.build(batch)
+        # sensitivity to fragmentation: the same pools and token count, tables made of fixed-length runs
+        if args.run_length_sweep and len(w.requests) == 1 and not stats["relayout"]:
+            tokens = w.requests[0].seq_len
+            nblk = wl.blocks_for(tokens, w.src.block_tokens)
+            straight = np.arange(nblk, dtype=np.int32)
+            sweep = {}
+            for side in ("both", "src", "dst"):
+                for run in (1, 2, 4, 8, 16, 64):
+                    rng = np.random.default_rng(w.seed + 1000 + run)
+                    ts = wl.fixed_run_table(rng, w.src.num_blocks, nblk, run) if side != "dst" else straight
+                    td = wl.fixed_run_table(rng, w.dst.num_blocks, nblk, run) if side != "src" else straight
+                    wr = wl.Workload(f"{w.name}-runs{run}-{side}", w.src, w.dst, [wl.Request(tokens, ts, td)],
+                                     w.dtype, w.seed, w.layer_begin, w.layer_end)
+                    # a descriptor ends where either side breaks, so one-sided cases have as many as two-sided ones
+                    y = G.GpuTransfer(wr, src, dst, stream=stream)
+                    y.build()
+                    y.plan.pull(sh)
+                    us = timed(lambda: y.plan.pull(sh), 10)
+                    sweep[f"{side}_runs_of_{run}"] = {"pull_us": us, "pct_of_peak": 2 * payload / us / 1e3 / PEAK_HBM_GBPS * 100,
+                                                     "descriptors": y.plan.stats(sh)["num_descriptors"]}
+                    y.close()
+            extras["run_length_sweep"] = sweep
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
         # one hipMemcpyAsync per (layer, K/V, block)
         if not stats["relayout"] and not args.no_slow_baselines:
             torch.cuda.synchronize()

@@ -142,6 +142,17 @@ def scattered_table(rng: np.random.Generator, pool_blocks: int, n: int) -> np.nd
     raise RuntimeError("could not scatter the table")
 
 
+def fixed_run_table(rng: np.random.Generator, pool_blocks: int, n: int, run: int) -> np.ndarray:
+    """n block ids as runs of exactly ``run`` physically consecutive ids (the last one may be
+    shorter); runs sit at random places and no run continues the one before it."""
+    slots = rng.permutation(pool_blocks // (2 * run))  # slot s = ids [2*run*s, 2*run*s + run)
+    runs = -(-n // run)
+    if runs > slots.size:
+        raise ValueError("pool too small for that many separate runs")
+    ids = np.concatenate([np.arange(2 * run * s, 2 * run * s + run) for s in slots[:runs]])
+    return ids[:n].astype(np.int32)
+
+
 def lognormal_lengths(rng: np.random.Generator, count: int, median: float = 1024.0,
                       sigma: float = 1.0, lo: int = 16, hi: int = 16384) -> np.ndarray:
     x = np.exp(rng.normal(np.log(median), sigma, size=count))

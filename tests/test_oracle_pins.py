@@ -179,6 +179,27 @@ def test_sizes_quoted_in_paper():
     assert n8 == int(GOLD["pieces_for_8k_tokens"])
 
 
+def test_runs_of_fixed_length_coalesce_to_one_transaction_per_run():
+    """Tables built from runs of exactly k adjacent blocks on both sides: the merged queue has one
+    transaction per run, each of k whole blocks (the last one what is left), in request order."""
+    g = wl.PoolGeometry(1, 512, 16, 2, 32, 2, wl.BHTD)
+    block = 16 * 2 * 32 * 2
+    for run in (1, 2, 3, 8):
+        rng = np.random.default_rng(run)
+        n = 50
+        st, dt = wl.fixed_run_table(rng, 512, n, run), wl.fixed_run_table(rng, 512, n, run)
+        assert len(set(st.tolist())) == n and len(set(dt.tolist())) == n
+        w = wl.Workload("t", g, g, [wl.Request(n * 16, st, dt)], "bf16", 0)
+        d = tl.oracle_plan_descriptors(w, 0, 0)
+        want = [min(run, n - i) * block for i in range(0, n, run)]
+        assert d[:, 2].tolist() == want
+        assert d[:, 0].tolist() == [int(st[i]) * block for i in range(0, n, run)]
+        assert d[:, 1].tolist() == [int(dt[i]) * block for i in range(0, n, run)]
+        # a straight table on one side does not merge what the other side breaks
+        w1 = wl.Workload("t", g, g, [wl.Request(n * 16, st, np.arange(n, dtype=np.int32))], "bf16", 0)
+        assert tl.oracle_plan_descriptors(w1, 0, 0)[:, 2].tolist() == want
+
+
 # ---------------------------------------------------------------- the copy itself
 
 def tiny_workloads():
