@@ -26,8 +26,9 @@ BTHD = "BTHD"  # inside a block: [token][head][dim]
 
 @dataclass(frozen=True)
 class PoolGeometry:
-    """One paged pool, stored as a single dense allocation [layer][kv][block][inner], or
-    [layer][block][kv][inner] when kv_adjacent (K and V of a block next to each other)."""
+    """One paged pool, stored as a single dense allocation [layer][kv][block][inner],
+    [layer][block][kv][inner] when kv_adjacent (K and V of a block next to each other), or
+    [block][layer][kv][inner] when block_major (everything a block holds in one piece)."""
     num_layers: int
     num_blocks: int
     block_tokens: int
@@ -36,6 +37,7 @@ class PoolGeometry:
     elem_bytes: int
     layout: str = BHTD
     kv_adjacent: bool = False
+    block_major: bool = False
 
     @property
     def tile_elems(self) -> int:
@@ -43,19 +45,21 @@ class PoolGeometry:
 
     @property
     def stride_block(self) -> int:
+        if self.block_major:
+            return 2 * self.num_layers * self.tile_elems
         return (2 if self.kv_adjacent else 1) * self.tile_elems
 
     @property
     def stride_kv(self) -> int:
-        return self.tile_elems if self.kv_adjacent else self.num_blocks * self.tile_elems
+        return self.tile_elems if (self.kv_adjacent or self.block_major) else self.num_blocks * self.tile_elems
 
     @property
     def stride_layer(self) -> int:
-        return 2 * self.num_blocks * self.tile_elems
+        return 2 * self.tile_elems if self.block_major else 2 * self.num_blocks * self.tile_elems
 
     @property
     def total_elems(self) -> int:
-        return self.num_layers * self.stride_layer
+        return 2 * self.num_layers * self.num_blocks * self.tile_elems
 
     @property
     def total_bytes(self) -> int:

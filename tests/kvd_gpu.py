@@ -29,7 +29,7 @@ def device_random_pool(g: wl.PoolGeometry, dtype: str, seed: int) -> torch.Tenso
     gen = torch.Generator(device=DEV)
     gen.manual_seed(seed)
     td = torch.float16 if dtype == "fp16" else torch.bfloat16
-    v = t.view(td).view(g.num_layers, g.stride_layer)
+    v = t.view(td).view(g.num_layers, -1)  # filled in num_layers equal parts
     for layer in range(g.num_layers):
         v[layer].normal_(generator=gen)
     return t

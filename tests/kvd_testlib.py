@@ -61,6 +61,38 @@ def oracle_plan_descriptors(w: wl.Workload, layer: int, kv: int) -> np.ndarray:
     return merged
 
 
+def oracle_plan_descriptors_block_major(w: wl.Workload) -> np.ndarray:
+    """Coalesced read transactions of the whole batch when the layer tensors are queued block by
+    block: for every piece of a request (tokens that share one block on both sides), the
+    transactions of layer_begin, layer_begin+1, ... in turn.  In pools that keep all layers of a
+    block together that is the order in which consecutive ranges continue each other, so section
+    4.2 merges a block's layers.  Offsets are relative to the pool."""
+    tmin = min(w.src.block_tokens, w.dst.block_tokens)
+    s_all, d_all = oracle_tensors(w.src, None), oracle_tensors(w.dst, None)
+    queue = []
+    for r in w.requests:
+        per_layer = {}
+        for layer in range(w.layer_begin, w.layer_end):
+            t = orc.request_transactions(s_all[layer], d_all[layer], -1, r.src_table, r.dst_table, r.seq_len)
+            t[:, 0] += layer * w.src.stride_layer * w.src.elem_bytes
+            t[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
+            per_layer[layer] = t
+        # where each piece's transactions end inside a layer's list: the list of the request cut
+        # after that piece is a prefix of the full list (pieces are enumerated independently)
+        ends = [len(orc.request_transactions(s_all[w.layer_begin], d_all[w.layer_begin], -1, r.src_table,
+                                             r.dst_table, min(t1, r.seq_len)))
+                for t1 in range(tmin, r.seq_len + tmin, tmin)]
+        assert ends[-1] == len(per_layer[w.layer_begin])
+        lo = 0
+        for hi in ends:
+            for layer in range(w.layer_begin, w.layer_end):
+                assert len(per_layer[layer]) == ends[-1]
+                queue.append(per_layer[layer][lo:hi])
+            lo = hi
+    q = np.concatenate(queue) if queue else np.zeros((0, 3), np.int64)
+    return orc.coalesce(q)
+
+
 # ------------------------------------------------------------------ brute force (tiny inputs)
 
 def _inner_index(layout: str, tb: int, hk: int, tok: int, head: int) -> int:

@@ -54,7 +54,10 @@ def pin_checks():
               pins.test_round_trip_is_identity_on_valid_tokens, pins.test_identity_tables_reduce_to_memcpy]
     for w in pins.tiny_workloads():
         checks.append(lambda w=w: pins.test_oracle_equals_brute_force_and_writes_each_element_once(w))
-    checks.append(lambda: pins.test_unique_ids_arrive_where_reshape_says("BHTD", "BTHD", 16, 32))
+    checks.append(lambda: pins.test_unique_ids_arrive_where_reshape_says("BHTD", "BTHD", 16, 32, (False, False)))
+    checks.append(lambda: pins.test_unique_ids_arrive_where_reshape_says("BHTD", "BHTD", 8, 16, (True, True)))
+    checks.append(pins.test_block_major_pools_coalesce_a_block_over_all_its_layers)
+    checks.append(pins.test_runs_of_fixed_length_coalesce_to_one_transaction_per_run)
     return checks
 
 

@@ -3,6 +3,8 @@ worked examples (tests/golden/paper_worked_example.txt), closed forms, an indepe
 element-by-element brute force, numpy's own reshape addressing, and invariants of a copy."""
 import os
 
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -200,6 +202,40 @@ def test_runs_of_fixed_length_coalesce_to_one_transaction_per_run():
         assert tl.oracle_plan_descriptors(w1, 0, 0)[:, 2].tolist() == want
 
 
+def test_block_major_pools_coalesce_a_block_over_all_its_layers():
+    """Pools that keep every layer of a block together, layer tensors queued block by block: a run
+    of r adjacent whole blocks is ONE transaction of r * layers * (K + V) tiles; a ragged last
+    block adds one range per (layer, K/V, head)."""
+    layers, hk = 3, 2
+    g = wl.PoolGeometry(layers, 64, 4, hk, 8, 2, wl.BHTD, block_major=True)
+    tile = 4 * hk * 8 * 2
+    block_bytes = layers * 2 * tile
+    st = np.array([10, 11, 12, 40, 41, 7], np.int32)
+    dt = np.array([20, 21, 22, 50, 51, 9], np.int32)
+    w = wl.Workload("t", g, g, [wl.Request(24, st, dt)], "bf16", 0)
+    d = tl.oracle_plan_descriptors_block_major(w)
+    assert d.tolist() == [[10 * block_bytes, 20 * block_bytes, 3 * block_bytes],
+                          [40 * block_bytes, 50 * block_bytes, 2 * block_bytes],
+                          [7 * block_bytes, 9 * block_bytes, block_bytes]]
+    # layers 1..2 only: the range starts one layer into the block and two blocks no longer touch
+    w12 = wl.Workload("t", g, g, [wl.Request(24, st, dt)], "bf16", 0, layer_begin=1, layer_end=3)
+    d = tl.oracle_plan_descriptors_block_major(w12)
+    assert len(d) == 6 and set(d[:, 2].tolist()) == {2 * 2 * tile}
+    assert d[0].tolist() == [10 * block_bytes + 2 * tile, 20 * block_bytes + 2 * tile, 4 * tile]
+    # ragged tail (22 tokens: the last block holds 2 of 4 slots): per (layer, K/V, head) ranges of 2 rows
+    wr = wl.Workload("t", g, g, [wl.Request(22, st, dt)], "bf16", 0)
+    d = tl.oracle_plan_descriptors_block_major(wr)
+    assert len(d) == 2 + layers * 2 * hk
+    assert set(d[2:, 2].tolist()) == {2 * 8 * 2}
+    assert d[:, 2].sum() == 22 * layers * 2 * hk * 8 * 2
+    # the same queue order in layer-major pools merges nothing at all (consecutive entries belong to
+    # different layers, far apart), while the layer-by-layer order merges the runs of each tensor
+    gl = wl.PoolGeometry(layers, 64, 4, hk, 8, 2, wl.BHTD)
+    wlm = wl.Workload("t", gl, gl, [wl.Request(24, st, dt)], "bf16", 0)
+    assert len(tl.oracle_plan_descriptors_block_major(wlm)) == 6 * layers * 2
+    assert len(tl.oracle_plan_descriptors(wlm, 0, 0)) == 3
+
+
 # ---------------------------------------------------------------- the copy itself
 
 def tiny_workloads():
@@ -227,6 +263,14 @@ def tiny_workloads():
     out.append(wl.Workload("tiny-layers", g, g, [
         wl.Request(7, perm_s[:2].astype(np.int32), perm_d[:2].astype(np.int32))], "bf16", 7,
         layer_begin=1, layer_end=2))
+    # pools that keep all layers of a block together, on both sides and on one side only
+    gb = wl.PoolGeometry(3, 8, 4, 2, 8, 2, wl.BHTD, block_major=True)
+    out.append(wl.Workload("tiny-block-major", gb, gb, [
+        wl.Request(10, perm_s[:3].astype(np.int32), perm_d[:3].astype(np.int32))], "bf16", 7,
+        layer_begin=1, layer_end=3))
+    gb2 = wl.PoolGeometry(2, 8, 4, 2, 8, 2, wl.BHTD, block_major=True)
+    out.append(wl.Workload("tiny-block-major-src", gb2, g, [
+        wl.Request(10, perm_s[:3].astype(np.int32), perm_d[:3].astype(np.int32))], "bf16", 7))
     # four-byte elements
     g4 = wl.PoolGeometry(1, 6, 4, 2, 4, 4, wl.BHTD)
     out.append(wl.Workload("tiny-e4", g4, g4, [
@@ -267,22 +311,30 @@ def test_oracle_equals_brute_force_and_writes_each_element_once(w):
 
 def _view(g, flat):
     """numpy's own addressing of the pool: reshape, no stride arithmetic of ours."""
+    if g.block_major:
+        if g.layout == wl.BHTD:
+            v = flat.reshape(g.num_blocks, g.num_layers, 2, g.num_kv_heads, g.block_tokens, g.head_dim)
+        else:
+            v = flat.reshape(g.num_blocks, g.num_layers, 2, g.block_tokens, g.num_kv_heads,
+                             g.head_dim).transpose(0, 1, 2, 4, 3, 5)
+        return v.transpose(1, 2, 0, 3, 4, 5)  # -> [layer, kv, block, head, token, dim]
     if g.layout == wl.BHTD:
         return flat.reshape(g.num_layers, 2, g.num_blocks, g.num_kv_heads, g.block_tokens, g.head_dim)
     return flat.reshape(g.num_layers, 2, g.num_blocks, g.block_tokens, g.num_kv_heads,
                         g.head_dim).transpose(0, 1, 2, 4, 3, 5)  # -> [..., head, token, dim]
 
 
+@pytest.mark.parametrize("block_major", [(False, False), (True, True), (False, True)])
 @pytest.mark.parametrize("src_layout,dst_layout,tbs,tbd", [
     (wl.BHTD, wl.BHTD, 16, 16), (wl.BTHD, wl.BTHD, 8, 8), (wl.BHTD, wl.BTHD, 16, 32),
     (wl.BTHD, wl.BHTD, 32, 16), (wl.BHTD, wl.BHTD, 8, 16)])
-def test_unique_ids_arrive_where_reshape_says(src_layout, dst_layout, tbs, tbd):
+def test_unique_ids_arrive_where_reshape_says(src_layout, dst_layout, tbs, tbd, block_major):
     """Fill the source so that logical element (layer, kv, token, head, dim) holds its own id;
     after the pull, the destination read through numpy's reshape view must hold the same ids."""
     rng = np.random.default_rng(3)
     layers, hk, dd, tokens = 3, 3, 8, 75
-    gs = wl.PoolGeometry(layers, 16, tbs, hk, dd, 4, src_layout)
-    gd = wl.PoolGeometry(layers, 16 * tbs // tbd + 2, tbd, hk, dd, 4, dst_layout)
+    gs = wl.PoolGeometry(layers, 16, tbs, hk, dd, 4, src_layout, block_major=block_major[0])
+    gd = wl.PoolGeometry(layers, 16 * tbs // tbd + 2, tbd, hk, dd, 4, dst_layout, block_major=block_major[1])
     st = wl.permutation_table(rng, gs.num_blocks, wl.blocks_for(tokens, tbs))
     dt = wl.permutation_table(rng, gd.num_blocks, wl.blocks_for(tokens, tbd))
     src = np.zeros(gs.total_elems, np.uint32)
@@ -335,7 +387,7 @@ def test_config1_shapes():
     assert orc.transfer_bytes(128, 2, 4, 64, 2) == 256 * 1024
 
 
-@pytest.mark.parametrize("seed", range(25))
+@pytest.mark.parametrize("seed", range(40))
 def test_oracle_equals_brute_force_on_random_tiny_geometries(seed):
     """Random small shapes: inner orders, block-size ratios, K/V placement, element widths, layer ranges."""
     rng = np.random.default_rng(900 + seed)
@@ -350,6 +402,9 @@ def test_oracle_equals_brute_force_on_random_tiny_geometries(seed):
                          str(rng.choice([wl.BHTD, wl.BTHD])), bool(rng.random() < 0.4))
     l0 = int(rng.integers(0, layers))
     l1 = int(rng.integers(l0 + 1, layers + 1))
+    if seed >= 15:  # the later seeds also draw pools that keep all layers of a block together
+        gs = dataclasses.replace(gs, block_major=bool(rng.random() < 0.5))
+        gd = dataclasses.replace(gd, block_major=bool(rng.random() < 0.5))
     w = wl.Workload("rand", gs, gd, [wl.Request(tokens, wl.permutation_table(rng, gs.num_blocks, wl.blocks_for(tokens, tbs)),
                                                 wl.permutation_table(rng, gd.num_blocks, wl.blocks_for(tokens, tbd)))],
                     "bf16", seed, l0, l1)
