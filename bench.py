@@ -263,6 +263,22 @@ def main() -> int:
                     sweep[f"{side}_runs_of_{run}"] = {"pull_us": us, "pct_of_peak": 2 * payload / us / 1e3 / PEAK_HBM_GBPS * 100,
                                                      "descriptors": y.plan.stats(sh)["num_descriptors"]}
                     y.close()
+            # the same bytes described as block-major pools ([block][layer][K/V]): a lone block is one range over all layers
+            import dataclasses
+            gbm = dataclasses.replace(w.src, block_major=True)
+            for run in (1, 2):
+                rng = np.random.default_rng(w.seed + 2000 + run)
+                wr = wl.Workload(f"{w.name}-block-major-runs{run}", gbm, gbm,
+                                 [wl.Request(tokens, wl.fixed_run_table(rng, gbm.num_blocks, nblk, run),
+                                             wl.fixed_run_table(rng, gbm.num_blocks, nblk, run))],
+                                 w.dtype, w.seed, w.layer_begin, w.layer_end)
+                y = G.GpuTransfer(wr, src, dst, stream=stream)
+                y.build()
+                y.plan.pull(sh)
+                us = timed(lambda: y.plan.pull(sh), 10)
+                sweep[f"block_major_both_runs_of_{run}"] = {"pull_us": us, "pct_of_peak": 2 * payload / us / 1e3 / PEAK_HBM_GBPS * 100,
+                                                             "descriptors": y.plan.stats(sh)["num_descriptors"]}
+                y.close()
             extras["run_length_sweep"] = sweep
             x.plan.reset()
             x.build(batch)

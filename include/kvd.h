@@ -96,7 +96,8 @@ typedef struct kvd_plan kvd_plan_t;
 /* A coalesced read transaction of the byte-copy path, relative to (layer 0, K): the copy for
  * (layer, kv) adds layer*stride_layer*elem_bytes + kv*stride_kv*elem_bytes of the respective
  * pool to both offsets.  In plans whose K and V are adjacent on both sides (see kvd_plan_create)
- * a transaction may span K and V and only the layer offset is added. */
+ * a transaction may span K and V and only the layer offset is added; in plans over block-major
+ * pools a transaction spans the request's layers too and its offsets are final. */
 typedef struct {
     uint64_t src_offset; /* bytes from the source pool's base       */
     uint64_t dst_offset; /* bytes from the destination pool's base  */
@@ -143,6 +144,13 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out);
  * When K and V of a block are neighbours in memory on both sides (stride_kv equals the elements
  * of one block) and the inner order is the same, a block's K and V are one byte range and merge
  * like any other contiguous ranges (section 4.1).
+ * When, in addition, the layers of a block are neighbours on both sides (block-major pools:
+ * stride_layer equals K plus V of one block, stride_block covers all layers), a request's layer
+ * tensors are queued block by block, so that everything the request moves of a block is one byte
+ * range (a ragged last block: one range per layer, K/V and head) and runs of adjacent blocks merge
+ * over all layers.  Such plans count transactions, descriptors and work items (kvd_stats_t) for
+ * the whole request, not per (layer, kv).  Needs each whole pool within 64 GiB; larger block-major
+ * pools are handled layer by layer like any other strides.
  * Errors: KVD_ERR_INVALID (null, zero capacity), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
  * elem_bytes differ; block sizes of which neither divides the other), KVD_ERR_ALIAS (the byte
  * ranges of the two pools overlap).

@@ -72,6 +72,10 @@ struct Item {
 struct Header {
     uint32_t n_desc;
     uint32_t n_items;
+    // what the last build left for kvd_expand_kernel: descriptors [exp_desc, n_desc) cover work
+    // items [exp_item, n_items), which are not written yet
+    uint32_t exp_desc;
+    uint32_t exp_item;
 };
 
 // Exact unsigned division by a run-time constant through multiply-high and shifts
@@ -112,6 +116,9 @@ struct Geo {
 // ------------------------------------------------------------------ build: translate + coalesce + expand
 
 constexpr uint32_t kMaxBatch = 512;  // requests one launch of the build kernel can take
+// Builds that add at most this many work items write them from the build kernel itself; larger
+// ones leave that to a second, wide launch (one workgroup would take about 1 us per thousand items).
+constexpr uint32_t kInlineItems = 8192;
 
 // One request of a batch, as the build kernel sees it.
 struct ReqDev {
@@ -129,11 +136,14 @@ struct BuildArgs {
     Item *items;
     Header *hdr;
     uint32_t n_req;
+    uint32_t base_src16;       // added to every offset: the first layer's place inside a block when
+    uint32_t base_dst16;       // the layers are folded into the block (0 otherwise)
     uint32_t n_txn;            // read transactions of the whole batch per (layer, K/V)
     uint32_t layers;           // layer_begin | num_layers << 16
     uint32_t fresh;            // 1: the plan is empty (header contents are stale)
     uint32_t may_merge_prev;   // 1: the previous request moves the same layers
     uint32_t no_coalesce;
+    uint32_t expand_inline;    // 1: this workgroup also writes the work items (few of them)
 };
 
 struct Txn {
@@ -168,8 +178,8 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, const 
     const uint32_t ntok = min(g.piece_tokens, rq.seq_len - t0);
     const uint32_t sb_i = fdiv(t0, g.div_tb_src), db_i = fdiv(t0, g.div_tb_dst);
     const uint32_t st0 = t0 - sb_i * g.tb_src, dt0 = t0 - db_i * g.tb_dst;
-    const uint32_t sbase = (uint32_t)a.tables_src[rq.table_off_src + sb_i] * g.src_block16;
-    const uint32_t dbase = (uint32_t)a.tables_dst[rq.table_off_dst + db_i] * g.dst_block16;
+    const uint32_t sbase = (uint32_t)a.tables_src[rq.table_off_src + sb_i] * g.src_block16 + a.base_src16;
+    const uint32_t dbase = (uint32_t)a.tables_dst[rq.table_off_dst + db_i] * g.dst_block16 + a.base_dst16;
     Txn t;
     t.meta = 0;
     if (g.mode == kSpanTokenMajor) {
@@ -356,7 +366,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     // expand descriptors [from, n1) into work items [first_item, n_items), a window of
     // descriptors at a time with their prefixes staged in LDS for the item -> descriptor search
     constexpr uint32_t kWin = 2 * kBuildThreads;
-    for (uint32_t w0 = from; w0 < n1; w0 += kWin) {
+    for (uint32_t w0 = from; a.expand_inline && w0 < n1; w0 += kWin) {
         const uint32_t nw = min(kWin, n1 - w0);
         for (uint32_t i = tid; i < nw; i += kBuildThreads) s_buf[i] = a.desc[w0 + i].prefix;
         __syncthreads();
@@ -376,9 +386,33 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         __syncthreads();
     }
     if (tid == 0) {
+        // Left to kvd_expand_kernel when there are many items.  An extended descriptor keeps the
+        // items it had; only its last one, which may have been short, is written again.
+        uint32_t exp_item = first_item;
+        if (had_open) exp_item = a.hdr->n_items - 1;
         a.hdr->n_desc = n1;
         a.hdr->n_items = n_items;
+        a.hdr->exp_desc = from;
+        a.hdr->exp_item = a.expand_inline ? n_items : exp_item;
     }
+}
+
+// The expansion of descriptors into work items for builds with many items: one lane per item,
+// the item's descriptor found by a search over the descriptors' item prefixes.
+// grid * 256 >= the number of items the build added + 1.
+__global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc, Item *items, const Header *hdr,
+                                                         uint32_t layers)
+{
+    const Header h = *hdr;
+    const uint32_t c = h.exp_item + blockIdx.x * 256 + threadIdx.x;
+    if (c >= h.n_items) return;
+    uint32_t lo = h.exp_desc, hi = h.n_desc;  // largest i with prefix[i] <= c
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (desc[mid].prefix <= c) lo = mid; else hi = mid;
+    }
+    const Desc d = desc[lo];
+    items[c] = make_item(g, d, c - d.prefix, layers);
 }
 
 // ------------------------------------------------------------------ pull
@@ -664,6 +698,11 @@ struct kvd_plan {
     kvd_pool_desc_t src, dst;
     uint32_t max_requests, max_total_blocks, flags;
     Geo geo;
+    // Block-major pools on both sides ([block][layer][K/V][...], every layer of a block adjacent):
+    // the layers a request moves are folded into the head axis as well, so a whole block is one
+    // byte range over all of them.  planes_per_layer = what one layer adds to that axis.
+    bool fold_layers;
+    uint32_t planes_per_layer;
     uint64_t max_txns, max_items;
     // host bookkeeping
     std::vector<ReqHost> reqs;
@@ -890,6 +929,15 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     } else {
         g.mode = (s.layout == KVD_LAYOUT_BHTD) ? kRelayoutHT2TH : kRelayoutTH2HT;
     }
+    // layers adjacent too (stride_layer = K + V of one block) and the whole pool within reach of a
+    // 32-bit unit offset: a block's layers form one range, in layer order
+    p->planes_per_layer = g.hk;
+    p->fold_layers = g.kv_shift == 0 &&
+                     (uint64_t)s.stride_layer == 2 * (uint64_t)s.stride_kv && (uint64_t)d.stride_layer == 2 * (uint64_t)d.stride_kv &&
+                     (uint64_t)s.num_blocks * s.stride_block * e < (1ull << 36) &&
+                     (uint64_t)d.num_blocks * d.stride_block * e < (1ull << 36) &&
+                     (uint64_t)g.hk * std::min(s.num_layers, d.num_layers) <= (1u << 20);
+    const uint32_t hk_max = p->fold_layers ? g.hk * std::min(s.num_layers, d.num_layers) : g.hk;
     g.rows_per_item = g.du <= kChunkUnits ? kChunkUnits / g.du : 0;
     if ((flags & KVD_PLAN_WHOLE_BLOCKS) && s.block_tokens != d.block_tokens) {
         delete p;
@@ -903,11 +951,11 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     // upper bounds of what the plan can hold: read transactions and work items
     const uint64_t pieces_max = (uint64_t)max_total_blocks * (tmax / tmin);
     if (g.mode == kSpanHeadMajor)
-        p->max_txns = (g.tb_src == g.tb_dst) ? pieces_max + (uint64_t)max_requests * g.hk
-                                             : pieces_max * g.hk;
+        p->max_txns = (g.tb_src == g.tb_dst) ? pieces_max + (uint64_t)max_requests * hk_max
+                                             : pieces_max * hk_max;
     else
         p->max_txns = pieces_max;
-    const uint64_t units_max = pieces_max * tmin * g.hk * g.du;
+    const uint64_t units_max = pieces_max * tmin * hk_max * g.du;
     if (g.mode >= kRelayoutHT2TH)
         p->max_items = pieces_max * tmin * g.hk / g.rows_per_item + p->max_txns + 1;
     else
@@ -957,7 +1005,15 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         return fail(KVD_ERR_RANGE, "layer range [%u, %u) outside a pool", layer_begin, layer_end);
     if (n_requests == 0) return KVD_OK;
     if (!src_tbls || !dst_tbls || !n_src || !n_dst || !seq_lens) return fail(KVD_ERR_INVALID, "null argument");
-    const Geo &g = p->geo;
+    // with the layers folded into the block, this call's layer range sets how many planes a block has
+    const uint32_t n_layers = layer_end - layer_begin;
+    Geo folded = p->geo;
+    if (p->fold_layers) {
+        folded.hk = p->planes_per_layer * n_layers;
+        folded.div_hk = make_fastdiv(folded.hk);
+    }
+    const Geo &g = folded;
+    const uint32_t slab_layers = p->fold_layers ? 1u : n_layers;  // layers left for the pull kernel to step through
 
     // whole-block mode moves every slot of the last block too (the block-granular transfer of
     // section 4.1); block sizes are equal then
@@ -1045,10 +1101,10 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         for (uint32_t i = 0; i < r.n_dst; ++i) p->dst_used[(uint32_t)dst_tbls[k][i]] = 1;
         p->used_src += r.n_src;
         p->used_dst += r.n_dst;
-        p->payload_bytes += ((uint64_t)seq_len * (layer_end - layer_begin) * g.hk * g.du * kUnitBytes) << g.kv_shift;
+        p->payload_bytes += ((uint64_t)seq_len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
         p->reqs.push_back(r);
     }
-    p->max_layers = std::max(p->max_layers, layer_end - layer_begin);
+    p->max_layers = std::max(p->max_layers, slab_layers);
     for (size_t b0 = first_new; b0 < p->reqs.size(); b0 += kMaxBatch) {
         const uint32_t nb = (uint32_t)std::min<size_t>(kMaxBatch, p->reqs.size() - b0);
         uint32_t batch_txn = 0, batch_items = 0;
@@ -1069,13 +1125,21 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         a.items = p->items_dev;
         a.hdr = p->hdr_dev;
         a.n_req = nb;
+        a.base_src16 = p->fold_layers ? (uint32_t)(layer_begin * g.src_layer_bytes / kUnitBytes) : 0u;
+        a.base_dst16 = p->fold_layers ? (uint32_t)(layer_begin * g.dst_layer_bytes / kUnitBytes) : 0u;
         a.n_txn = batch_txn;
-        a.layers = layer_begin | ((layer_end - layer_begin) << 16);
+        a.layers = p->fold_layers ? (1u << 16) : (layer_begin | (n_layers << 16));
         a.fresh = (b0 == 0) ? 1u : 0u;
         a.may_merge_prev = (b0 > first_new || same_layers) ? 1u : 0u;
         a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
+        a.expand_inline = batch_items <= kInlineItems ? 1u : 0u;
         hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
         hipError_t launch = hipGetLastError();
+        if (launch == hipSuccess && !a.expand_inline) {
+            hipLaunchKernelGGL(kvd_expand_kernel, dim3(batch_items / 256 + 1), dim3(256), 0, (hipStream_t)stream, g,
+                               p->desc_dev, p->items_dev, p->hdr_dev, a.layers);
+            launch = hipGetLastError();
+        }
         if (launch == hipSuccess) launch = hipEventRecord(p->build_done, (hipStream_t)stream);
         if (launch != hipSuccess) {
             // the plan's device state no longer matches the host's: drop everything queued
@@ -1114,7 +1178,8 @@ int kvd_pull(kvd_plan_t *p, void *stream)
         for (const ReqHost &r : p->reqs)
             if (r.layer_begin != p->reqs[0].layer_begin || r.layer_end != p->reqs[0].layer_end)
                 return fail(KVD_ERR_MISMATCH, "the persistent form needs one layer range for the whole plan");
-        const uint32_t layers = p->reqs[0].layer_begin | ((p->reqs[0].layer_end - p->reqs[0].layer_begin) << 16);
+        const uint32_t layers = p->fold_layers ? (1u << 16)
+                                               : (p->reqs[0].layer_begin | ((p->reqs[0].layer_end - p->reqs[0].layer_begin) << 16));
         hipLaunchKernelGGL(kvd_pull_persistent_kernel, dim3((uint32_t)p->num_cus * 2), dim3(1024), 0,
                            (hipStream_t)stream, p->geo, a, p->desc_dev, layers);
     } else {
@@ -1185,12 +1250,15 @@ int kvd_pull_blockwise_memcpy(kvd_plan_t *p, void *stream)
         return fail(KVD_ERR_MISMATCH, "blockwise memcpy baseline needs equal layout and block size");
     const uint64_t e = p->src.elem_bytes;
     const uint64_t row = (uint64_t)g.du * kUnitBytes;  // bytes of one (token, head) row
-    const uint64_t tile = (uint64_t)g.tb_src * g.hk * row;
     const char *sb = (const char *)p->src.base;
     char *db = (char *)p->dst.base;
     for (const ReqHost &r : p->reqs) {
         const uint32_t whole = r.seq_len / g.tb_src, tail = r.seq_len % g.tb_src;
-        for (uint32_t layer = r.layer_begin; layer < r.layer_end; ++layer)
+        // layers folded into the block: one copy covers the request's layers of a block
+        const uint32_t hk = p->fold_layers ? p->planes_per_layer * (r.layer_end - r.layer_begin) : g.hk;
+        const uint32_t layer_stop = p->fold_layers ? r.layer_begin + 1 : r.layer_end;
+        const uint64_t tile = (uint64_t)g.tb_src * hk * row;
+        for (uint32_t layer = r.layer_begin; layer < layer_stop; ++layer)
             for (uint32_t kv = 0; kv < (1u << g.kv_shift); ++kv) {
                 const uint64_t so = layer * g.src_layer_bytes + kv * g.src_kv_bytes;
                 const uint64_t dof = layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
@@ -1205,7 +1273,7 @@ int kvd_pull_blockwise_memcpy(kvd_plan_t *p, void *stream)
                     if (g.mode == kSpanTokenMajor) {
                         KVD_HIP(hipMemcpyAsync(db + d, sb + s, tail * g.hk * row, hipMemcpyDeviceToDevice, (hipStream_t)stream));
                     } else {
-                        for (uint32_t h = 0; h < g.hk; ++h)
+                        for (uint32_t h = 0; h < hk; ++h)
                             KVD_HIP(hipMemcpyAsync(db + d + h * g.tb_dst * row, sb + s + h * g.tb_src * row,
                                                    tail * row, hipMemcpyDeviceToDevice, (hipStream_t)stream));
                     }

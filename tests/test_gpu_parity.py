@@ -2,6 +2,8 @@
 
 Small cases compare whole pools element by element; the full-size configurations compare
 sampled layers with the oracle and check size-independent properties on every layer."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -110,6 +112,39 @@ def test_batch_larger_than_one_launch_takes():
     assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), tl.oracle_plan_descriptors(w, 0, 0))
     G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "701 requests")
     x.close()
+
+
+def test_wide_expansion_continues_an_open_descriptor():
+    """A long request (its work items are written by the separate wide launch) that continues the
+    previous request's last descriptor, whose last work item was a short one; then another long
+    request that may not merge (other layers)."""
+    g = wl.PoolGeometry(2, 40000, 16, 1, 80, 2, wl.BHTD)  # 2560-byte blocks: 1.6 blocks per work item
+    n_b = 14000
+    a = wl.Request(3 * 16, np.arange(100, 103, dtype=np.int32), np.arange(200, 203, dtype=np.int32))
+    tail_s = np.array([30000, 30001, 5, 39999], np.int32)
+    tail_d = np.array([31000, 31001, 39999, 7], np.int32)
+    b = wl.Request((n_b + 4) * 16 - 3, np.concatenate([np.arange(103, 103 + n_b, dtype=np.int32), tail_s]),
+                   np.concatenate([np.arange(203, 203 + n_b, dtype=np.int32), tail_d]))
+    c = wl.Request(n_b * 16, np.arange(15000, 15000 + n_b, dtype=np.int32), np.arange(16000, 16000 + n_b, dtype=np.int32))
+    src_host = host_src(wl.Workload("wide", g, g, [], "bf16", 51))
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), 3, 2 * n_b + 16)
+    plan.build_descriptors(a.src_table, a.dst_table, a.seq_len, 0, 2)
+    assert plan.stats()["num_work_items"] == 2                      # 7680 bytes: one whole item and a short one
+    plan.build_descriptors(b.src_table, b.dst_table, b.seq_len, 0, 2)
+    st = plan.stats()
+    assert st["num_descriptors"] == 4 and st["num_work_items"] > 8192
+    want_ab = tl.oracle_plan_descriptors(wl.Workload("ab", g, g, [a, b], "bf16", 51), 0, 0)
+    assert np.array_equal(plan.descriptors(), want_ab) and want_ab[0, 2] == (3 + n_b) * 2560
+    plan.build_descriptors(c.src_table, c.dst_table, c.seq_len, 1, 2)
+    assert plan.stats()["num_descriptors"] == 5
+    plan.pull()
+    torch.cuda.synchronize()
+    want = wl.host_pool_sentinel(g)
+    tl.oracle_pull_workload(wl.Workload("ab", g, g, [a, b], "bf16", 51), src_host, want)
+    tl.oracle_pull_workload(wl.Workload("c", g, g, [c], "bf16", 51, 1, 2), src_host, want)
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "wide expansion")
+    plan.close()
 
 
 def test_no_coalesce_flag_keeps_every_transaction_and_same_bytes():
@@ -467,8 +502,101 @@ def test_one_side_with_adjacent_k_and_v(adj_src, adj_dst):
     x.close()
 
 
-@pytest.mark.parametrize("g", [small_geom(), small_geom(layout=wl.BTHD), small_geom(kv_adjacent=True)],
-                         ids=["hm", "tm", "kv-adjacent"])
+@pytest.mark.parametrize("gs,gd", [
+    (small_geom(block_major=True), small_geom(block_major=True)),
+    (small_geom(block_major=True, layout=wl.BTHD), small_geom(block_major=True, layout=wl.BTHD)),
+    (small_geom(block_major=True, layout=wl.BTHD), small_geom(block_major=True, layout=wl.BTHD, block_tokens=32, num_blocks=48)),
+    (small_geom(block_major=True, block_tokens=32, num_blocks=48), small_geom(block_major=True, block_tokens=8, num_blocks=192)),
+    (small_geom(block_major=True, num_kv_heads=1), small_geom(block_major=True, num_kv_heads=1, layout=wl.BTHD)),
+], ids=["hm", "tm", "tm16-32", "hm32-8", "one-head"])
+@pytest.mark.parametrize("tokens", [333, 1024])
+@pytest.mark.parametrize("layers", [(0, 3), (1, 3), (1, 2)])
+def test_block_major_pools(gs, gd, tokens, layers):
+    """Pools that keep all layers of a block together: what a request moves of a block is one byte range."""
+    w = wl.Workload("block-major", gs, gd, [_frag_request(gs, gd, tokens, 41)], "bf16", 41, layers[0], layers[1])
+    x = G.run_and_compare(w, host_src(w))
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    assert np.array_equal(got, tl.oracle_plan_descriptors_block_major(w))
+    st = x.plan.stats(x.stream.cuda_stream)
+    nl = layers[1] - layers[0]
+    assert st["payload_bytes"] == tokens * nl * 2 * gs.num_kv_heads * gs.head_dim * 2 == got[:, 2].sum()
+    if gs.block_tokens == gd.block_tokens and tokens % 16 == 0 and nl == 3:
+        r = w.requests[0]
+        breaks = np.count_nonzero((r.src_table[1:] != r.src_table[:-1] + 1) | (r.dst_table[1:] != r.dst_table[:-1] + 1))
+        assert len(got) == 1 + breaks
+    x.close()
+
+
+@pytest.mark.parametrize("major_src,major_dst", [(True, False), (False, True)])
+def test_one_side_block_major(major_src, major_dst):
+    """Only one pool keeps a block's layers together: nothing merges across layers, K and V still do."""
+    gs = small_geom(block_major=major_src, kv_adjacent=not major_src)
+    gd = small_geom(block_major=major_dst, kv_adjacent=not major_dst)
+    w = wl.Workload("block-major-one-side", gs, gd, [_frag_request(gs, gd, 700, 42)], "bf16", 42)
+    x = G.run_and_compare(w, host_src(w))
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), tl.oracle_plan_descriptors(w, 0, -1))
+    x.close()
+
+
+def test_block_major_batch_mixed_layer_ranges_and_baselines():
+    """Several requests in one block-major plan: a batch, then requests with other layer ranges; the
+    comparison forms of the pull move the same bytes."""
+    g = small_geom(block_major=True, num_blocks=256)
+    rng = np.random.default_rng(43)
+    free_s, free_d = np.ones(256, bool), np.ones(256, bool)
+    lens = [100, 16, 333, 7, 64]
+    reqs = [wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, 16), 4),
+                       wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, 16), 4)) for t in lens]
+    ranges = [(0, 3), (0, 3), (0, 3), (1, 3), (2, 3)]
+    src_host = rng.integers(0, 256, size=g.total_bytes, dtype=np.uint8)
+    want = wl.host_pool_sentinel(g)
+    for r, (l0, l1) in zip(reqs, ranges):
+        tl.oracle_pull_workload(wl.Workload("one", g, g, [r], "bf16", 0, l0, l1), src_host, want)
+    for flags in (0, kvd.KVD_PLAN_NO_COALESCE):
+        src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+        plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), len(reqs), 64, flags)
+        plan.build_descriptors_batch([r.src_table for r in reqs[:3]], [r.dst_table for r in reqs[:3]], lens[:3], 0, 3)
+        for r, (l0, l1) in zip(reqs[3:], ranges[3:]):
+            plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1)
+        plan.pull()
+        torch.cuda.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"block-major batch, flags {flags}")
+        if flags == 0:
+            wb = wl.Workload("batch", g, g, reqs[:3], "bf16", 0)
+            head = tl.oracle_plan_descriptors_block_major(wb)
+            assert np.array_equal(plan.descriptors()[:len(head)], head)
+        # staged and per-block memcpy forms of the same plan
+        for form in ("staged", "memcpy"):
+            dst2 = G.device_sentinel_pool(g)
+            plan2 = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst2.data_ptr(), g), len(reqs), 64, flags)
+            for r, (l0, l1) in zip(reqs, ranges):
+                plan2.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1)
+            if form == "staged":
+                send = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+                recv = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+                plan2.pull_staged(send.data_ptr(), recv.data_ptr(), 1 << 16)
+            else:
+                plan2.pull_blockwise_memcpy()
+            torch.cuda.synchronize()
+            G.assert_bytes_equal(dst2.cpu().numpy(), want, f"block-major {form}, flags {flags}")
+            plan2.close()
+        plan.close()
+    # persistent form: one layer range for the whole plan
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    want1 = wl.host_pool_sentinel(g)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), len(reqs), 64, kvd.KVD_PLAN_PERSISTENT)
+    for r in reqs:
+        plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, 1, 3)
+        tl.oracle_pull_workload(wl.Workload("one", g, g, [r], "bf16", 0, 1, 3), src_host, want1)
+    plan.pull()
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want1, "block-major persistent")
+    plan.close()
+
+
+@pytest.mark.parametrize("g", [small_geom(), small_geom(layout=wl.BTHD), small_geom(kv_adjacent=True),
+                               small_geom(block_major=True)],
+                         ids=["hm", "tm", "kv-adjacent", "block-major"])
 def test_whole_block_mode_moves_every_slot_of_the_last_block(g):
     tokens = 16 * 9 + 5
     w = wl.Workload("whole", g, g, [_frag_request(g, g, tokens, 33)], "bf16", 33)
@@ -481,8 +609,9 @@ def test_whole_block_mode_moves_every_slot_of_the_last_block(g):
     G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w_full, src_host), "whole-block mode")
     st = x.plan.stats(x.stream.cuda_stream)
     assert st["payload_bytes"] == 160 * g.num_layers * 2 * g.num_kv_heads * g.head_dim * 2
-    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream),
-                          tl.oracle_plan_descriptors(w_full, 0, -1 if g.kv_adjacent else 0))
+    want = tl.oracle_plan_descriptors_block_major(w_full) if g.block_major else \
+        tl.oracle_plan_descriptors(w_full, 0, -1 if g.kv_adjacent else 0)
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), want)
     x.close()
 
 
@@ -570,10 +699,14 @@ def _random_case(seed):
         flags |= kvd.KVD_PLAN_PERSISTENT
     if tb_s == tb_d and rng.random() < 0.25:
         flags |= kvd.KVD_PLAN_WHOLE_BLOCKS
-    return gs, gd, reqs, ranges, flags, bool(uniform and n_req > 1 and rng.random() < 0.5)
+    batch = bool(uniform and n_req > 1 and rng.random() < 0.5)
+    if seed >= 60:  # the later seeds also draw pools that keep all layers of a block together
+        gs = dataclasses.replace(gs, block_major=bool(rng.random() < 0.6))
+        gd = dataclasses.replace(gd, block_major=bool(rng.random() < 0.6))
+    return gs, gd, reqs, ranges, flags, batch
 
 
-@pytest.mark.parametrize("seed", range(60))
+@pytest.mark.parametrize("seed", range(100))
 def test_random_small_transfers(seed):
     gs, gd, reqs, ranges, flags, batch = _random_case(seed)
     say(f"seed {seed}: {gs} -> {gd}, lens {[r.seq_len for r in reqs]}, layers {ranges}, flags {flags}, batch {batch}")
@@ -651,3 +784,42 @@ def test_full_config4():
 
 def test_full_config5():
     _check_full(wl.config5(), [0, 13, 31])
+
+
+def test_full_config2_block_major_with_every_block_alone():
+    """cfg2's shape in block-major pools, every block alone on both sides: one 2 MiB range per block."""
+    base = wl.config2()
+    g = dataclasses.replace(base.src, block_major=True)
+    rng = np.random.default_rng(77)
+    n = wl.blocks_for(8192 - 5, 16)
+    w = wl.Workload("cfg2-block-major-lone", g, g, [wl.Request(8192 - 5, wl.scattered_table(rng, g.num_blocks, n),
+                                                              wl.scattered_table(rng, g.num_blocks, n))], "bf16", 77)
+    say(f"{w.name}: allocating pools 2 x {g.total_bytes / 2**30:.1f} GiB")
+    src = G.device_random_pool(g, "bf16", 77)
+    dst = G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst).run()
+    st = x.plan.stats(x.stream.cuda_stream)
+    say(f"{w.name}: {st}")
+    r = w.requests[0]
+    assert st["num_descriptors"] == (n - 1) + g.num_layers * 2 * g.num_kv_heads
+    assert st["payload_bytes"] == r.seq_len * g.num_layers * 2 * g.num_kv_heads * g.head_dim * 2
+    # exactly the payload's words differ from the sentinel
+    dv = dst.view(torch.int16).view(g.num_blocks, g.num_layers, 2, -1)
+    sv = src.view(torch.int16).view(g.num_blocks, g.num_layers, 2, -1)
+    nonsent = sum(int((dv[b0:b0 + 1024] != wl.SENTINEL16).sum()) for b0 in range(0, g.num_blocks, 1024))
+    assert nonsent == st["payload_bytes"] // 2
+    # whole blocks arrive as whole blocks, all layers
+    si = torch.from_numpy(r.src_table[:n - 1].astype(np.int64)).cuda()
+    di = torch.from_numpy(r.dst_table[:n - 1].astype(np.int64)).cuda()
+    for lo in range(0, n - 1, 128):
+        assert torch.equal(dv[di[lo:lo + 128]], sv[si[lo:lo + 128]])
+    # oracle, element by element, on sampled layers: torch's strided view hands the layer over as a
+    # one-layer pool in [kv][block] order, which the oracle addresses with that pool's own strides
+    g1 = wl.PoolGeometry(1, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes, g.layout)
+    w1 = wl.Workload(w.name, g1, g1, w.requests, "bf16", 77)
+    for layer in (0, 13, 31):
+        say(f"{w.name}: oracle on layer {layer}")
+        src_host = sv[:, layer].permute(1, 0, 2).contiguous().view(torch.uint8).view(-1).cpu().numpy()
+        got = dv[:, layer].permute(1, 0, 2).contiguous().view(torch.uint8).view(-1).cpu().numpy()
+        G.assert_bytes_equal(got, G.oracle_expected(w1, src_host), f"{w.name} layer {layer}")
+    x.close()
