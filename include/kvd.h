@@ -235,8 +235,10 @@ int kvd_pull_staged(kvd_plan_t *plan, void *send_buffer, void *recv_buffer, uint
  */
 int kvd_pull_blockwise_memcpy(kvd_plan_t *plan, void *stream);
 
-/* Forget all requests of the plan (waits for the plan's own staging copies, not for pulls:
- * the caller must not reset while a build or pull of this plan is still running). */
+/* Forget all requests of the plan.  Waits (a short spin on a word in pinned host memory that the
+ * build kernel sets) until the builds enqueued so far have read the plan's copy of the block
+ * tables; it does not wait for pulls: the caller must not enqueue a new build of this plan on a
+ * stream where it could overtake a pull of the old contents. */
 int kvd_plan_reset(kvd_plan_t *plan);
 
 /* Counters of the plan.  Synchronises `stream` (the one the builds were enqueued on) to read

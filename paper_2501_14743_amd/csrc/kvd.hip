@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -144,6 +145,8 @@ struct BuildArgs {
     uint32_t may_merge_prev;   // 1: the previous request moves the same layers
     uint32_t no_coalesce;
     uint32_t expand_inline;    // 1: this workgroup also writes the work items (few of them)
+    uint32_t *done;            // pinned host word that receives `seq` once the tables have been read
+    uint32_t seq;
 };
 
 struct Txn {
@@ -326,6 +329,10 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         have_prev = true;
         __syncthreads();
     }
+
+    // The host's block tables and request list are not read again: tell the host, which may then
+    // overwrite them for the next build while this one is still running.
+    if (tid == 0) __hip_atomic_store(a.done, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 
     // work-item prefix over the descriptors that are new or were extended
     const uint32_t n1 = runs;
@@ -722,8 +729,13 @@ struct kvd_plan {
     bool order_stale;      // requests were appended since ordered_dev was last written
     uint32_t order_shift;  // log2 of the region size in 16-byte units
     Header *hdr_dev;
-    hipEvent_t build_done;
-    bool build_pending;
+    // Completion of the build kernels, as far as the host's tables are concerned: every launch
+    // carries a sequence number and stores it into a pinned host word when it has read them.
+    // (An event recorded between the build and the pull would cost a few microseconds of every
+    // step on the GPU's queue.)
+    uint32_t *done_host, *done_dev;
+    uint32_t build_seq;
+    hipStream_t build_stream;
 };
 
 namespace {
@@ -817,15 +829,38 @@ int ensure_allocated(kvd_plan *p)
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->ordered_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
-    KVD_HIP(hipEventCreateWithFlags(&p->build_done, hipEventDisableTiming));
+    KVD_HIP(hipHostMalloc((void **)&p->done_host, 64, hipHostMallocMapped));
+    KVD_HIP(hipHostGetDevicePointer((void **)&p->done_dev, p->done_host, 0));
+    *p->done_host = 0;
+    p->build_seq = 0;
+    p->build_stream = nullptr;
     p->allocated = true;
+    return KVD_OK;
+}
+
+// Wait until the last build kernel of the plan has read the host's tables.  Normally a short spin
+// on the pinned word; after two seconds without it, the stream is synchronised to see what happened.
+int wait_for_builds(kvd_plan *p)
+{
+    if (!p->allocated) return KVD_OK;
+    volatile uint32_t *done = p->done_host;
+    if (*done == p->build_seq) return KVD_OK;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint32_t spins = 1;; ++spins) {
+        if (*done == p->build_seq) return KVD_OK;
+        __builtin_ia32_pause();
+        if ((spins & 0xFFF) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) break;
+    }
+    KVD_HIP(hipStreamSynchronize(p->build_stream));
+    if (*done != p->build_seq) return fail(KVD_ERR_HIP, "the build kernel did not report completion");
     return KVD_OK;
 }
 
 void release_plan(kvd_plan *p)
 {
     if (p->allocated) {
-        if (p->build_pending) (void)hipEventSynchronize(p->build_done);
+        (void)wait_for_builds(p);
+        (void)hipHostFree(p->done_host);
         (void)hipHostFree(p->tables_src);
         (void)hipHostFree(p->tables_dst);
         (void)hipHostFree(p->reqs_pinned);
@@ -833,7 +868,6 @@ void release_plan(kvd_plan *p)
         (void)hipFree(p->items_dev);
         (void)hipFree(p->ordered_dev);
         (void)hipFree(p->hdr_dev);
-        (void)hipEventDestroy(p->build_done);
     }
     p->tag = 0;
     delete p;
@@ -974,7 +1008,6 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     p->dst_used.assign(d.num_blocks, 0);
     p->reqs.reserve(max_requests);
     p->allocated = false;
-    p->build_pending = false;
     *out = p;
     return KVD_OK;
 }
@@ -982,10 +1015,8 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
 int kvd_plan_reset(kvd_plan_t *p)
 {
     if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
-    if (p->build_pending) {
-        KVD_HIP(hipEventSynchronize(p->build_done));
-        p->build_pending = false;
-    }
+    const int rc = wait_for_builds(p);
+    if (rc != KVD_OK) return rc;
     for (const ReqHost &r : p->reqs)
         for (uint32_t i = 0; i < r.n_dst; ++i)
             p->dst_used[(uint32_t)p->tables_dst[r.table_off_dst + i]] = 0;
@@ -1133,6 +1164,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         a.may_merge_prev = (b0 > first_new || same_layers) ? 1u : 0u;
         a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
         a.expand_inline = batch_items <= kInlineItems ? 1u : 0u;
+        a.done = p->done_dev;
+        a.seq = ++p->build_seq;
+        p->build_stream = (hipStream_t)stream;
         hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
         hipError_t launch = hipGetLastError();
         if (launch == hipSuccess && !a.expand_inline) {
@@ -1140,14 +1174,14 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
                                p->desc_dev, p->items_dev, p->hdr_dev, a.layers);
             launch = hipGetLastError();
         }
-        if (launch == hipSuccess) launch = hipEventRecord(p->build_done, (hipStream_t)stream);
         if (launch != hipSuccess) {
-            // the plan's device state no longer matches the host's: drop everything queued
-            p->build_pending = true;
+            // the plan's device state no longer matches the host's: let what was queued before
+            // finish, then drop everything (no kernel will report this sequence number)
+            (void)hipStreamSynchronize((hipStream_t)stream);
+            *p->done_host = p->build_seq;
             (void)kvd_plan_reset(p);
             return fail(KVD_ERR_HIP, "launch of the build kernel failed (plan was reset): %s", hipGetErrorString(launch));
         }
-        p->build_pending = true;
         p->order_stale = true;
         p->txns_total += batch_txn;
         p->item_bound += batch_items;
