@@ -6,6 +6,7 @@
 //                      4.1), coalescing of queued ranges with a wave64 ballot + prefix scan
 //                      (section 4.2), then expansion of the coalesced ranges into a table of
 //                      fixed 4 KiB work items.
+//   kvd_expand_kernel  that expansion as a wide launch of its own, for builds with many items.
 //   kvd_pull_kernel    moves the bytes: one small workgroup per (work item, layer, K/V), one
 //                      16-byte load and one 16-byte store per lane, non-temporal.  The
 //                      hardware dispatcher hands the work items out in table order, which
