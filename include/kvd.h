@@ -62,8 +62,8 @@ typedef enum {
  * axes inside a block are dense.  Strides count elements.
  * Requirements (else KVD_ERR_INVALID): base, stride_*xelem_bytes and head_dim*elem_bytes are
  * multiples of 16 bytes; elem_bytes is 1, 2, 4 or 8; stride_block >= elements of one block;
- * block_tokens <= 1024.  The block axis of one (layer, kv) slab may span at most 64 GiB
- * (KVD_ERR_RANGE).
+ * block_tokens <= 1024.  The block axis of one (layer, kv) slab may span at most 64 GiB and
+ * every stride must be below 2^44 elements (KVD_ERR_RANGE).
  */
 typedef struct {
     void *base; /* DEVICE pointer, borrowed for the pool's lifetime */
@@ -178,7 +178,7 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
  *
  * Errors (checked on the host before anything is enqueued; the plan is unchanged on error):
  * KVD_ERR_INVALID (null, layer_begin >= layer_end), KVD_ERR_RANGE (block id outside its pool,
- * layer range outside either pool, a table shorter than ceil(seq_len / T)), KVD_ERR_ALIAS (a
+ * layer range outside either pool, a table shorter than ceil(seq_len / T), seq_len above 2^30), KVD_ERR_ALIAS (a
  * destination block already used in this plan, or twice in this request; repeated source
  * blocks are allowed), KVD_ERR_CAPACITY, KVD_ERR_HIP.
  */

@@ -754,6 +754,8 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
     if (d.num_layers > 32767) return fail(KVD_ERR_INVALID, "num_layers above 32767");
     if (d.stride_layer < 0 || d.stride_kv < 0 || d.stride_block < 0)
         return fail(KVD_ERR_INVALID, "negative stride");
+    if (d.stride_layer >= (1ll << 44) || d.stride_kv >= (1ll << 44) || d.stride_block >= (1ll << 44))
+        return fail(KVD_ERR_RANGE, "stride of 2^44 elements or more");
     const uint64_t e = d.elem_bytes;
     const uint64_t tile = (uint64_t)d.block_tokens * d.num_kv_heads * d.head_dim;
     if ((uint64_t)d.stride_block < tile)
@@ -1055,6 +1057,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
     // 1. everything that can be checked without touching the plan
     uint64_t add_src = 0, add_dst = 0, add_txn = 0, add_items = 0, add_reqs = 0;
     for (uint32_t k = 0; k < n_requests; ++k) {
+        if (seq_lens[k] > (1u << 30)) return fail(KVD_ERR_RANGE, "request %u: seq_len %u above 2^30", k, seq_lens[k]);
         const uint32_t seq_len = effective_len(seq_lens[k]);
         if (seq_len == 0) continue;
         const int32_t *st = src_tbls[k], *dt = dst_tbls[k];

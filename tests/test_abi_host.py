@@ -67,6 +67,7 @@ def test_pool_create_rejects_bad_metadata():
     kvd.Pool(FAKE_SRC, g, 2 * g.tile_elems, g.tile_elems, 2 * g.num_layers * g.tile_elems).close()
     expect(kvd.KVD_ERR_INVALID, kvd.kvd_pool_create, FAKE_SRC, 2, 64, 16, 4, 64, 2, 7, 1 << 20, 1 << 19, 4096)
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8))
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, g, 1 << 44, g.stride_kv, g.stride_block)   # absurd stride
     p = kvd.Pool(FAKE_SRC, g)
     assert p.handle
     p.close()
@@ -110,6 +111,7 @@ def test_build_descriptors_validates_before_launching():
     msg = expect(kvd.KVD_ERR_ALIAS, plan.build_descriptors, ok, dup, 128, 0, 2)   # destination block twice
     assert "destination block 2" in msg
     expect(kvd.KVD_ERR_CAPACITY, plan.build_descriptors, np.arange(9), np.arange(9), 144, 0, 2)
+    expect(kvd.KVD_ERR_RANGE, plan.build_descriptors, ok, ok, (1 << 30) + 1, 0, 2)  # seq_len beyond the limit
     # entries beyond ceil(seq_len / block_tokens) are ignored, even invalid ones
     long_tbl = np.array([0, 1, 99999], dtype=np.int32)
     # seq_len 0 appends nothing and succeeds, whatever the tables hold
