@@ -347,13 +347,20 @@ def _strides(kind, g):
         return g.num_blocks * sb, skv, sb
     if kind == "block-major":     # [block][layer][kv]: every block holds all its layers
         return 2 * tile, tile, 2 * g.num_layers * tile
+    if kind == "block-major-padded":  # the same with a tile of padding behind every block: blocks never touch
+        return 2 * tile, tile, 2 * g.num_layers * tile + tile
+    if kind == "block-major-loose":   # [block][layer][kv] with a gap between a block's layers: only K and V touch
+        return 3 * tile, tile, 3 * g.num_layers * tile
     if kind == "kv-outermost":    # [kv][layer][block]
         return g.num_blocks * tile, g.num_layers * g.num_blocks * tile, tile
     raise ValueError(kind)
 
 
 @pytest.mark.parametrize("kind_src,kind_dst", [("padded", "padded"), ("block-major", "block-major"),
-                                               ("kv-outermost", "block-major"), ("block-major", "padded")])
+                                               ("kv-outermost", "block-major"), ("block-major", "padded"),
+                                               ("block-major-padded", "block-major"),
+                                               ("block-major-loose", "block-major-loose"),
+                                               ("block-major", "block-major-loose")])
 def test_pools_described_only_by_their_strides(kind_src, kind_dst):
     g = small_geom(num_layers=2, num_blocks=32)
     rng = np.random.default_rng(8)
