@@ -5,9 +5,9 @@
 Both runs must be `bench.py ... --copy-calibration`, which also launches the plain copy kernel on
 1 GiB.  FETCH_SIZE / WRITE_SIZE are reported per dispatch in nominal KiB; each is scaled by
 (1 GiB in KiB) / (what the same counter reads for the plain 1 GiB copy), so the result does not
-depend on the counter's unit.  Writes `hbm_traffic.json` next to this file; bench.py reports its
-`traffic_bytes_per_launch` only while the kernel source (comments and white space aside) still has the
-recorded hash.
+depend on the counter's unit.  Adds the workload's record to `hbm_traffic.json` next to this file
+(one record per workload); bench.py reports a record's `traffic_bytes_per_launch` only while the
+kernel source (comments and white space aside) still has the hash stored with that record.
 """
 from __future__ import annotations
 
@@ -43,13 +43,17 @@ def source_hash() -> str:
 
 def load_record(workload: str):
     """The recorded traffic for `workload`, or None if there is none for the current kernel source."""
-    if not os.path.exists(RECORD):
-        return None
-    with open(RECORD) as f:
-        rec = json.load(f)
-    if rec.get("kernel_source_sha256") != source_hash() or rec.get("workload") != workload:
+    rec = _load_all().get(workload)
+    if rec is None or rec.get("kernel_source_sha256") != source_hash():
         return None
     return rec
+
+
+def _load_all() -> dict:
+    if not os.path.exists(RECORD):
+        return {}
+    with open(RECORD) as f:
+        return json.load(f).get("records", {})
 
 
 def _mean_counter(path: str, counter: str, kernel_substr: str) -> tuple[float, int]:
@@ -84,8 +88,10 @@ def main(argv) -> int:
         "read_bytes_per_launch": read_b, "write_bytes_per_launch": write_b,
         "traffic_bytes_per_launch": read_b + write_b,
     }
+    records = _load_all()
+    records[workload] = rec
     with open(RECORD, "w") as f:
-        json.dump(rec, f, indent=1)
+        json.dump({"records": records}, f, indent=1)
     print(json.dumps(rec, indent=1))
     return 0
 
