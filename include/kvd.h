@@ -62,8 +62,9 @@ typedef enum {
  * axes inside a block are dense.  Strides count elements.
  * Requirements (else KVD_ERR_INVALID): base, stride_*xelem_bytes and head_dim*elem_bytes are
  * multiples of 16 bytes; elem_bytes is 1, 2, 4 or 8; stride_block >= elements of one block;
- * block_tokens <= 1024.  The block axis of one (layer, kv) slab may span at most 64 GiB and
- * every stride must be below 2^44 elements (KVD_ERR_RANGE).
+ * block_tokens <= 1024.  Every stride must be below 2^44 elements, stride_block below 64 GiB and
+ * the block axis of one (layer, kv) slab below 2^50 bytes (KVD_ERR_RANGE); a plan accepts a block
+ * axis above 64 GiB only for block-major pools on both sides (see kvd_plan_create).
  */
 typedef struct {
     void *base; /* DEVICE pointer, borrowed for the pool's lifetime */
@@ -89,6 +90,8 @@ typedef struct kvd_plan kvd_plan_t;
                                    block sizes, else KVD_ERR_MISMATCH)                              */
 #define KVD_PLAN_QUEUE_ORDER 8u  /* never group the work items by destination region: kvd_pull walks them
                                    in queue order whatever the plan looks like (ablation)           */
+#define KVD_PLAN_WIDE_OFFSETS 16u /* block-major plans: carry 48-bit offsets even where 32 bits reach the whole
+                                   pool (the form pools above 64 GiB get by themselves); for testing  */
 #define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a persistent grid that stages the coalesced descriptors
                                    in LDS and walks them wave by wave, instead of one small workgroup
                                    per work item (for comparison; slower; one layer range per plan) */
@@ -149,11 +152,15 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out);
  * tensors are queued block by block, so that everything the request moves of a block is one byte
  * range (a ragged last block: one range per layer, K/V and head) and runs of adjacent blocks merge
  * over all layers.  Such plans count transactions, descriptors and work items (kvd_stats_t) for
- * the whole request, not per (layer, kv).  Needs each whole pool within 64 GiB; larger block-major
- * pools are handled layer by layer like any other strides.
+ * the whole request, not per (layer, kv).  Offsets inside such a plan have 32 bits (of 16-byte
+ * units) while both pools stay within 64 GiB and 48 bits beyond; with 48-bit offsets a descriptor
+ * never continues across a multiple of 32 GiB from either pool's base (its length keeps 32 bits),
+ * so a run that crosses one is two descriptors.
  * Errors: KVD_ERR_INVALID (null, zero capacity), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
- * elem_bytes differ; block sizes of which neither divides the other), KVD_ERR_ALIAS (the byte
- * ranges of the two pools overlap).
+ * elem_bytes differ; block sizes of which neither divides the other; KVD_PLAN_WIDE_OFFSETS or a
+ * pool above 64 GiB with KVD_PLAN_PERSISTENT, KVD_PLAN_WIDE_OFFSETS without block-major pools),
+ * KVD_ERR_RANGE (a block axis above 64 GiB in a plan that is not block-major on both sides with
+ * the same inner order), KVD_ERR_ALIAS (the byte ranges of the two pools overlap).
  */
 int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_requests,
                     uint32_t max_total_blocks, uint32_t flags, kvd_plan_t **out);

@@ -49,8 +49,10 @@ enum Mode : uint32_t {
     kRelayoutTH2HT = 3    // source [token][head][dim] -> destination [head][token][dim]
 };
 
-// Coalesced read transaction, 16 bytes.  Offsets and lengths count 16-byte units.
-//   byte-copy path: a = first unit past the end on the source side (length = a - src16)
+// Coalesced read transaction, 16 bytes.  Offsets and lengths count 16-byte units.  src16 / dst16
+// are the low 32 bits of the offsets; bits 32..47 (pools above 64 GiB) sit in a parallel array.
+//   byte-copy path: a = low 32 bits of the first unit past the end on the source side
+//                   (length = a - src16, modulo 2^32)
 //   re-layout path: a = src_token | dst_token << 10 | num_tokens << 20; src16/dst16 = block base
 struct Desc {
     uint32_t src16;
@@ -63,7 +65,8 @@ struct Desc {
 //   byte-copy path: n = units (1..256) starting at src16 / dst16
 //   re-layout path: n = first_row | (rows - 1) << 20, rows of one (token, head) each, numbered
 //                   token-major inside the piece; src16 / dst16 = the piece's first token
-//   layers = layer_begin | num_layers << 16
+//   layers = layer_begin | num_layers << 16; with 48-bit offsets (Geo::wide, one slab only):
+//            bits 32..47 of the source offset | those of the destination offset << 16
 struct Item {
     uint32_t src16;
     uint32_t dst16;
@@ -111,6 +114,7 @@ struct Geo {
     uint32_t piece_tokens;              // min(tb_src, tb_dst): tokens that share a block on both sides
     uint32_t rows_per_item;             // re-layout: (token, head) rows per work item = 256 / du
     uint32_t kv_shift;                  // 1: K and V are separate slabs; 0: K/V folded into the head axis
+    uint32_t wide;                      // 1: offsets have 48 bits (layers folded too, so there is one slab)
     uint32_t mode;
     FastDiv div_du, div_hk, div_tb_src, div_tb_dst;
 };
@@ -135,6 +139,7 @@ struct BuildArgs {
     const ReqDev *reqs;         // the batch (device-visible pinned host memory)
     ReqDev first;               // copy of reqs[0]: a single request needs no extra host read
     Desc *desc;
+    uint32_t *desc_hi;          // per descriptor: bits 32..47 of src offset | those of dst offset << 16
     Item *items;
     Header *hdr;
     uint32_t n_req;
@@ -151,7 +156,8 @@ struct BuildArgs {
 };
 
 struct Txn {
-    uint32_t s16, d16, len16, meta;
+    uint64_t s16, d16;
+    uint32_t len16, meta;
 };
 
 // Section 4.1: block id -> offset through the strides.  Transaction j of request rq, in the
@@ -182,8 +188,8 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, const 
     const uint32_t ntok = min(g.piece_tokens, rq.seq_len - t0);
     const uint32_t sb_i = fdiv(t0, g.div_tb_src), db_i = fdiv(t0, g.div_tb_dst);
     const uint32_t st0 = t0 - sb_i * g.tb_src, dt0 = t0 - db_i * g.tb_dst;
-    const uint32_t sbase = (uint32_t)a.tables_src[rq.table_off_src + sb_i] * g.src_block16 + a.base_src16;
-    const uint32_t dbase = (uint32_t)a.tables_dst[rq.table_off_dst + db_i] * g.dst_block16 + a.base_dst16;
+    const uint64_t sbase = (uint64_t)(uint32_t)a.tables_src[rq.table_off_src + sb_i] * g.src_block16 + a.base_src16;
+    const uint64_t dbase = (uint64_t)(uint32_t)a.tables_dst[rq.table_off_dst + db_i] * g.dst_block16 + a.base_dst16;
     Txn t;
     t.meta = 0;
     if (g.mode == kSpanTokenMajor) {
@@ -209,15 +215,18 @@ __device__ __forceinline__ Txn make_txn(const Geo &g, const BuildArgs &a, const 
     return t;
 }
 
-// Work item number cl of descriptor d.
-__device__ __forceinline__ Item make_item(const Geo &g, const Desc d, uint32_t cl, uint32_t layers)
+// Work item number cl of descriptor d (hi = the upper halves of its offsets).
+__device__ __forceinline__ Item make_item(const Geo &g, const Desc d, uint32_t hi, uint32_t cl, uint32_t layers)
 {
     Item it;
     it.layers = layers;
     if (g.mode < kRelayoutHT2TH) {
-        it.src16 = d.src16 + cl * kChunkUnits;
-        it.dst16 = d.dst16 + cl * kChunkUnits;
+        const uint64_t s = (((uint64_t)(hi & 0xFFFFu) << 32) | d.src16) + (uint64_t)cl * kChunkUnits;
+        const uint64_t t = (((uint64_t)(hi >> 16) << 32) | d.dst16) + (uint64_t)cl * kChunkUnits;
+        it.src16 = (uint32_t)s;
+        it.dst16 = (uint32_t)t;
         it.n = min(kChunkUnits, d.a - d.src16 - cl * kChunkUnits);
+        if (g.wide) it.layers = (uint32_t)(s >> 32) | ((uint32_t)(t >> 32) << 16);
     } else {
         const uint32_t st0 = d.a & 1023u, dt0 = (d.a >> 10) & 1023u, ntok = d.a >> 20;
         const uint32_t row0 = cl * g.rows_per_item;
@@ -240,8 +249,10 @@ __device__ __forceinline__ uint32_t desc_items(const Geo &g, const Desc &d)
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildArgs a)
 {
-    __shared__ uint32_t s_buf[2 * kBuildThreads];
-    uint32_t *const s_end_s = s_buf, *const s_end_d = s_buf + kBuildThreads;
+    __shared__ uint64_t s_end[2 * kBuildThreads];  // where every transaction of the tile ends, per side
+    uint64_t *const s_end_s = s_end, *const s_end_d = s_end + kBuildThreads;
+    uint32_t *const s_buf = (uint32_t *)s_end;     // the same memory as 4096 words, for the expansion
+    __shared__ uint64_t s_win[kBuildThreads];      // 2^31-unit windows the transactions start in
     __shared__ uint8_t s_brk[kBuildThreads];
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
     __shared__ ReqDev s_req[kMaxBatch];
@@ -258,12 +269,15 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     // The queue's last transaction so far: a new transaction that continues it on both sides
     // is merged into it, also when it belongs to another request (section 4.2).
     bool have_prev = false;
-    uint32_t prev_s = 0, prev_d = 0;
+    uint64_t prev_s = 0, prev_d = 0, prev_w = 0;
     if (n0 > 0 && !never_merge && a.may_merge_prev) {
-        Desc p = a.desc[n0 - 1];
+        const Desc p = a.desc[n0 - 1];
+        const uint32_t hi = a.desc_hi[n0 - 1];
+        const uint64_t s0 = ((uint64_t)(hi & 0xFFFFu) << 32) | p.src16, d0 = ((uint64_t)(hi >> 16) << 32) | p.dst16;
         have_prev = true;
-        prev_s = p.a;
-        prev_d = p.dst16 + (p.a - p.src16);
+        prev_s = s0 + (p.a - p.src16);
+        prev_d = d0 + (p.a - p.src16);
+        prev_w = g.wide ? (((s0 >> 31) << 32) | (d0 >> 31)) : 0ull;
     }
     const bool had_open = have_prev;
     uint32_t runs = n0;
@@ -284,21 +298,26 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             }
             t = make_txn(g, a, rq, j - rq.txn_begin);
         }
+        // With 48-bit offsets a descriptor's length must still fit 32 bits: its transactions all
+        // start in one 2^31-unit window (32 GiB) per side, so a run breaks where it enters the next one.
+        const uint64_t my_w = g.wide ? (((t.s16 >> 31) << 32) | (t.d16 >> 31)) : 0ull;
         s_end_s[tid] = t.s16 + t.len16;
         s_end_d[tid] = t.d16 + t.len16;
+        s_win[tid] = my_w;
         __syncthreads();
-        uint32_t ps = prev_s, pd = prev_d;
+        uint64_t ps = prev_s, pd = prev_d, pw = prev_w;
         bool hp = have_prev;
         if (tid > 0) {
             ps = s_end_s[tid - 1];
             pd = s_end_d[tid - 1];
+            pw = s_win[tid - 1];
             hp = true;
         }
         const uint32_t tile_last = min(kBuildThreads, a.n_txn - tile) - 1;
-        const uint32_t next_prev_s = s_end_s[tile_last], next_prev_d = s_end_d[tile_last];
+        const uint64_t next_prev_s = s_end_s[tile_last], next_prev_d = s_end_d[tile_last], next_prev_w = s_win[tile_last];
 
         // break flag: this transaction starts a new descriptor
-        const bool brk = valid && (never_merge || !hp || ps != t.s16 || pd != t.d16);
+        const bool brk = valid && (never_merge || !hp || ps != t.s16 || pd != t.d16 || pw != my_w);
         const uint64_t ballot = __ballot(brk);
         const uint32_t before = __popcll(ballot & ((1ull << lane) - 1ull));
         if (lane == 0) s_wave[wave] = __popcll(ballot);
@@ -315,18 +334,20 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             // descriptor this transaction belongs to = (breaks up to and including it) - 1
             const uint32_t run = runs + wave_prefix + before + (brk ? 1u : 0u) - 1u;
             if (brk) {
-                a.desc[run].src16 = t.s16;
-                a.desc[run].dst16 = t.d16;
+                a.desc[run].src16 = (uint32_t)t.s16;
+                a.desc[run].dst16 = (uint32_t)t.d16;
+                a.desc_hi[run] = (uint32_t)(t.s16 >> 32) | ((uint32_t)(t.d16 >> 32) << 16);
                 if (relayout) a.desc[run].a = t.meta;
             }
             // the last member of a descriptor (so far) records where it ends; a later tile or
             // a later request that continues it overwrites this
             const bool closes = (tid == tile_last) || s_brk[tid + 1];
-            if (!relayout && closes) a.desc[run].a = t.s16 + t.len16;
+            if (!relayout && closes) a.desc[run].a = (uint32_t)(t.s16 + t.len16);
         }
         runs += total;
         prev_s = next_prev_s;
         prev_d = next_prev_d;
+        prev_w = next_prev_w;
         have_prev = true;
         __syncthreads();
     }
@@ -388,7 +409,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             }
             const Desc d = a.desc[w0 + lo];
             const uint32_t cl = c - d.prefix;
-            const Item it = make_item(g, d, cl, a.layers);
+            const Item it = make_item(g, d, a.desc_hi[w0 + lo], cl, a.layers);
             a.items[c] = it;
         }
         __syncthreads();
@@ -408,8 +429,8 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
 // The expansion of descriptors into work items for builds with many items: one lane per item,
 // the item's descriptor found by a search over the descriptors' item prefixes.
 // grid * 256 >= the number of items the build added + 1.
-__global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc, Item *items, const Header *hdr,
-                                                         uint32_t layers)
+__global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc, const uint32_t *desc_hi, Item *items,
+                                                         const Header *hdr, uint32_t layers)
 {
     const Header h = *hdr;
     const uint32_t c = h.exp_item + blockIdx.x * 256 + threadIdx.x;
@@ -420,7 +441,7 @@ __global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc
         if (desc[mid].prefix <= c) lo = mid; else hi = mid;
     }
     const Desc d = desc[lo];
-    items[c] = make_item(g, d, c - d.prefix, layers);
+    items[c] = make_item(g, d, desc_hi[lo], c - d.prefix, layers);
 }
 
 // ------------------------------------------------------------------ pull
@@ -446,33 +467,41 @@ __device__ __forceinline__ void stream_store(u32x4 v, u32x4 *p)
 // Where lane unit u of work item `it` sits on both sides, in 16-byte units from the slab base.
 // False if the item has no such unit or does not take part in slab y.
 __device__ __forceinline__ bool unit_offsets(const Geo &g, const Item it, uint32_t y, uint32_t u,
-                                             uint32_t *s16, uint32_t *d16)
+                                             uint64_t *s16, uint64_t *d16)
 {
+    if (g.wide) {  // one slab; the item's last word holds the upper halves of the offsets
+        if (y > 0 || u >= it.n) return false;
+        *s16 = (((uint64_t)(it.layers & 0xFFFFu) << 32) | it.src16) + u;
+        *d16 = (((uint64_t)(it.layers >> 16) << 32) | it.dst16) + u;
+        return true;
+    }
     if (y >= (it.layers >> 16) << g.kv_shift) return false;
     if (g.mode < kRelayoutHT2TH) {
         if (u >= it.n) return false;
-        *s16 = it.src16 + u;
-        *d16 = it.dst16 + u;
+        *s16 = (uint64_t)it.src16 + u;
+        *d16 = (uint64_t)it.dst16 + u;
     } else {
         const uint32_t r = fdiv(u, g.div_du), x = u - r * g.du;
         if (r > (it.n >> 20)) return false;
         const uint32_t row = (it.n & 0xFFFFFu) + r;
         const uint32_t tok = fdiv(row, g.div_hk), head = row - tok * g.hk;
         const uint32_t in_ht_src = head * g.tb_src + tok, in_ht_dst = head * g.tb_dst + tok;
-        *s16 = it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
-        *d16 = it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
+        *s16 = (uint64_t)it.src16 + ((g.mode == kRelayoutHT2TH) ? in_ht_src : row) * g.du + x;
+        *d16 = (uint64_t)it.dst16 + ((g.mode == kRelayoutHT2TH) ? row : in_ht_dst) * g.du + x;
     }
     return true;
 }
 
 __device__ __forceinline__ const unsigned char *src_slab(const Geo &g, const PullArgs &a, const Item it, uint32_t y)
 {
+    if (g.wide) return a.src_base;
     const uint32_t layer = (it.layers & 0xFFFFu) + (y >> g.kv_shift), kv = y & g.kv_shift;
     return a.src_base + layer * g.src_layer_bytes + kv * g.src_kv_bytes;
 }
 
 __device__ __forceinline__ unsigned char *dst_slab(const Geo &g, const PullArgs &a, const Item it, uint32_t y)
 {
+    if (g.wide) return a.dst_base;
     const uint32_t layer = (it.layers & 0xFFFFu) + (y >> g.kv_shift), kv = y & g.kv_shift;
     return a.dst_base + layer * g.dst_layer_bytes + kv * g.dst_kv_bytes;
 }
@@ -481,7 +510,7 @@ __device__ __forceinline__ unsigned char *dst_slab(const Geo &g, const PullArgs 
 __device__ __forceinline__ void move_unit(const Geo &g, const PullArgs &a, const Item it, uint32_t y,
                                           uint32_t u)
 {
-    uint32_t s16, d16;
+    uint64_t s16, d16;
     if (!unit_offsets(g, it, y, u, &s16, &d16)) return;
     const unsigned char *sp = src_slab(g, a, it, y);
     unsigned char *dp = dst_slab(g, a, it, y);
@@ -499,7 +528,7 @@ __global__ __launch_bounds__(64) void kvd_stage_kernel(Geo g, PullArgs a, unsign
     const uint32_t c = blockIdx.x >> 2, u = (blockIdx.x & 3u) * 64 + threadIdx.x;
     if (c >= n) return;
     const Item it = a.items[first_item + c];
-    uint32_t s16, d16;
+    uint64_t s16, d16;
     if (!unit_offsets(g, it, y, u, &s16, &d16)) return;
     u32x4 *packed = (u32x4 *)(buffer + ((size_t)c * kChunkUnits + u) * kUnitBytes);
     if (GATHER)
@@ -549,7 +578,7 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
 constexpr uint32_t kOrderBuckets = 4096;
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *items, Item *ordered, const Header *hdr,
-                                                                   uint32_t shift)
+                                                                   uint32_t shift, uint32_t wide)
 {
     __shared__ uint32_t s_count[kOrderBuckets];
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
@@ -561,8 +590,11 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
     }
     for (uint32_t b = tid; b < kOrderBuckets; b += kBuildThreads) s_count[b] = 0;
     __syncthreads();
-    for (uint32_t i = tid; i < h.n_items; i += kBuildThreads)
-        atomicAdd(&s_count[min(items[i].dst16 >> shift, kOrderBuckets - 1)], 1u);
+    auto region = [&](const Item &it) {
+        const uint64_t d = wide ? (((uint64_t)(it.layers >> 16) << 32) | it.dst16) : (uint64_t)it.dst16;
+        return (uint32_t)min(d >> shift, (uint64_t)(kOrderBuckets - 1));
+    };
+    for (uint32_t i = tid; i < h.n_items; i += kBuildThreads) atomicAdd(&s_count[region(items[i])], 1u);
     __syncthreads();
     // exclusive scan of the bucket counts: four consecutive buckets per lane
     constexpr uint32_t kPer = kOrderBuckets / kBuildThreads;
@@ -590,7 +622,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
     __syncthreads();
     for (uint32_t i = tid; i < h.n_items; i += kBuildThreads) {
         const Item it = items[i];
-        ordered[atomicAdd(&s_count[min(it.dst16 >> shift, kOrderBuckets - 1)], 1u)] = it;
+        ordered[atomicAdd(&s_count[region(it)], 1u)] = it;
     }
 }
 
@@ -637,8 +669,8 @@ __global__ __launch_bounds__(1024) void kvd_pull_persistent_kernel(Geo g, PullAr
                 if (s_desc[mid].prefix <= c) lo = mid; else hi = mid;
             }
             const Desc d = s_desc[lo];
-            const Item it = make_item(g, d, c - d.prefix, layers);
-            uint32_t s16[4], d16[4];
+            const Item it = make_item(g, d, 0u, c - d.prefix, layers);  // 32-bit offsets only (checked by the host)
+            uint64_t s16[4], d16[4];
             bool ok[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) ok[k] = unit_offsets(g, it, 0, k * kWave + lane, &s16[k], &d16[k]);
@@ -701,6 +733,13 @@ struct kvd_pool {
     uint64_t extent_bytes;  // bytes from base that the metadata can reach
 };
 
+// Bytes the block axis of one (layer, K/V) slab spans.
+static uint64_t block_axis_bytes(const kvd_pool_desc_t &d)
+{
+    return ((uint64_t)(d.num_blocks - 1) * d.stride_block + (uint64_t)d.block_tokens * d.num_kv_heads * d.head_dim) *
+           d.elem_bytes;
+}
+
 struct kvd_plan {
     uint32_t tag;
     kvd_pool_desc_t src, dst;
@@ -725,6 +764,7 @@ struct kvd_plan {
     int32_t *tables_src_dev, *tables_dst_dev;
     ReqDev *reqs_pinned, *reqs_pinned_dev;  // one entry per request, same kind of memory
     Desc *desc_dev;
+    uint32_t *desc_hi_dev;  // upper halves of the descriptors' offsets (zero unless geo.wide)
     Item *items_dev;
     Item *ordered_dev;     // items grouped by destination region (plans of short descriptors)
     bool order_stale;      // requests were appended since ordered_dev was last written
@@ -768,9 +808,10 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
         return fail(KVD_ERR_INVALID, "head_dim*elem_bytes above 4096 bytes");
     if ((uint64_t)d.block_tokens * d.num_kv_heads > (1u << 20))
         return fail(KVD_ERR_INVALID, "block_tokens*num_kv_heads above 2^20");
+    if ((uint64_t)d.stride_block * e >= (1ull << 36)) return fail(KVD_ERR_RANGE, "stride_block of 64 GiB or more");
     const uint64_t block_axis = ((uint64_t)(d.num_blocks - 1) * d.stride_block + tile) * e;
-    if (block_axis >= (1ull << 36))
-        return fail(KVD_ERR_RANGE, "block axis of one slab spans more than 64 GiB");
+    if (block_axis >= (1ull << 50))
+        return fail(KVD_ERR_RANGE, "block axis spans more than 2^50 bytes");
     // the layer, K/V and block axes must nest without overlap, in whatever order the strides put them
     struct Axis { uint64_t n, stride; } ax[3] = {{d.num_layers, (uint64_t)d.stride_layer},
                                                  {2, (uint64_t)d.stride_kv},
@@ -829,6 +870,7 @@ int ensure_allocated(kvd_plan *p)
     KVD_HIP(hipHostMalloc((void **)&p->reqs_pinned, (size_t)p->max_requests * sizeof(ReqDev), hipHostMallocMapped));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->reqs_pinned_dev, p->reqs_pinned, 0));
     KVD_HIP(hipMalloc((void **)&p->desc_dev, (size_t)p->max_txns * sizeof(Desc)));
+    KVD_HIP(hipMalloc((void **)&p->desc_hi_dev, (size_t)p->max_txns * sizeof(uint32_t)));
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->ordered_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
@@ -868,6 +910,7 @@ void release_plan(kvd_plan *p)
         (void)hipHostFree(p->tables_dst);
         (void)hipHostFree(p->reqs_pinned);
         (void)hipFree(p->desc_dev);
+        (void)hipFree(p->desc_hi_dev);
         (void)hipFree(p->items_dev);
         (void)hipFree(p->ordered_dev);
         (void)hipFree(p->hdr_dev);
@@ -971,9 +1014,25 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     p->planes_per_layer = g.hk;
     p->fold_layers = g.kv_shift == 0 &&
                      (uint64_t)s.stride_layer == 2 * (uint64_t)s.stride_kv && (uint64_t)d.stride_layer == 2 * (uint64_t)d.stride_kv &&
-                     (uint64_t)s.num_blocks * s.stride_block * e < (1ull << 36) &&
-                     (uint64_t)d.num_blocks * d.stride_block * e < (1ull << 36) &&
                      (uint64_t)g.hk * std::min(s.num_layers, d.num_layers) <= (1u << 20);
+    // 32-bit unit offsets reach 64 GiB: enough for one slab of most pools.  A folded plan has one
+    // slab, the whole pool; beyond 64 GiB (or when asked to) it carries 48-bit offsets.
+    const bool beyond32 = (uint64_t)s.num_blocks * s.stride_block * e >= (1ull << 36) ||
+                          (uint64_t)d.num_blocks * d.stride_block * e >= (1ull << 36);
+    g.wide = (p->fold_layers && (beyond32 || (flags & KVD_PLAN_WIDE_OFFSETS))) ? 1u : 0u;
+    if (!p->fold_layers && (block_axis_bytes(s) >= (1ull << 36) || block_axis_bytes(d) >= (1ull << 36))) {
+        delete p;
+        return fail(KVD_ERR_RANGE, "a block axis that spans more than 64 GiB needs block-major pools with the same inner "
+                                   "order on both sides");
+    }
+    if ((flags & KVD_PLAN_WIDE_OFFSETS) && !p->fold_layers) {
+        delete p;
+        return fail(KVD_ERR_MISMATCH, "48-bit offsets are for block-major pools with the same inner order on both sides");
+    }
+    if ((flags & KVD_PLAN_PERSISTENT) && g.wide) {
+        delete p;
+        return fail(KVD_ERR_MISMATCH, "the persistent form has 32-bit offsets only");
+    }
     const uint32_t hk_max = p->fold_layers ? g.hk * std::min(s.num_layers, d.num_layers) : g.hk;
     g.rows_per_item = g.du <= kChunkUnits ? kChunkUnits / g.du : 0;
     if ((flags & KVD_PLAN_WHOLE_BLOCKS) && s.block_tokens != d.block_tokens) {
@@ -1157,6 +1216,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         a.reqs = p->reqs_pinned_dev + b0;
         a.first = p->reqs_pinned[b0];
         a.desc = p->desc_dev;
+        a.desc_hi = p->desc_hi_dev;
         a.items = p->items_dev;
         a.hdr = p->hdr_dev;
         a.n_req = nb;
@@ -1175,7 +1235,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         hipError_t launch = hipGetLastError();
         if (launch == hipSuccess && !a.expand_inline) {
             hipLaunchKernelGGL(kvd_expand_kernel, dim3(batch_items / 256 + 1), dim3(256), 0, (hipStream_t)stream, g,
-                               p->desc_dev, p->items_dev, p->hdr_dev, a.layers);
+                               p->desc_dev, p->desc_hi_dev, p->items_dev, p->hdr_dev, a.layers);
             launch = hipGetLastError();
         }
         if (launch != hipSuccess) {
@@ -1228,7 +1288,7 @@ int kvd_pull(kvd_plan_t *p, void *stream)
             p->item_bound * a.slabs >= (1u << 17)) {
             if (p->order_stale) {
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
-                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift);
+                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift, p->geo.wide);
                 KVD_HIP(hipGetLastError());
                 p->order_stale = false;
             }
@@ -1355,7 +1415,9 @@ int kvd_plan_get_descriptors(kvd_plan_t *p, void *stream, kvd_span_t *spans, kvd
     KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
     if (h.n_desc > p->max_txns) return fail(KVD_ERR_HIP, "corrupt plan header");
     std::vector<Desc> d(h.n_desc);
+    std::vector<uint32_t> hi(h.n_desc);
     KVD_HIP(hipMemcpy(d.data(), p->desc_dev, (size_t)h.n_desc * sizeof(Desc), hipMemcpyDeviceToHost));
+    KVD_HIP(hipMemcpy(hi.data(), p->desc_hi_dev, (size_t)h.n_desc * sizeof(uint32_t), hipMemcpyDeviceToHost));
     for (uint32_t i = 0; i < h.n_desc && i < cap; ++i) {
         if (relayout) {
             pieces[i].src_block = (int32_t)(d[i].src16 / p->geo.src_block16);
@@ -1364,8 +1426,8 @@ int kvd_plan_get_descriptors(kvd_plan_t *p, void *stream, kvd_span_t *spans, kvd
             pieces[i].dst_token = (d[i].a >> 10) & 1023u;
             pieces[i].num_tokens = d[i].a >> 20;
         } else {
-            spans[i].src_offset = (uint64_t)d[i].src16 * kUnitBytes;
-            spans[i].dst_offset = (uint64_t)d[i].dst16 * kUnitBytes;
+            spans[i].src_offset = (((uint64_t)(hi[i] & 0xFFFFu) << 32) | d[i].src16) * kUnitBytes;
+            spans[i].dst_offset = (((uint64_t)(hi[i] >> 16) << 32) | d[i].dst16) * kUnitBytes;
             spans[i].bytes = (uint64_t)(d[i].a - d[i].src16) * kUnitBytes;
         }
     }

@@ -66,7 +66,8 @@ def test_pool_create_rejects_bad_metadata():
     # any nesting order of the three axes is fine: blocks outermost, then layers, then K/V
     kvd.Pool(FAKE_SRC, g, 2 * g.tile_elems, g.tile_elems, 2 * g.num_layers * g.tile_elems).close()
     expect(kvd.KVD_ERR_INVALID, kvd.kvd_pool_create, FAKE_SRC, 2, 64, 16, 4, 64, 2, 7, 1 << 20, 1 << 19, 4096)
-    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8))
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 30, head_dim=2048, num_kv_heads=64))  # 2^53 bytes
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, g, g.stride_layer, g.stride_kv, 1 << 35)       # 64 GiB between blocks
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, g, 1 << 44, g.stride_kv, g.stride_block)   # absurd stride
     p = kvd.Pool(FAKE_SRC, g)
     assert p.handle
@@ -89,6 +90,15 @@ def test_plan_create_rejects_mismatch_and_overlap():
     expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 1, 0)
     # touching but not overlapping is fine
     kvd.Plan(s, kvd.Pool(FAKE_SRC + g.total_bytes, g), 1, 8).close()
+    # a slab of 512 GiB is a legal pool, but only block-major pools on both sides can use one in a plan
+    big = geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8)
+    big_bm = geom(num_blocks=1 << 24, head_dim=128, num_kv_heads=8, block_major=True)
+    far = FAKE_SRC + (1 << 44)
+    expect(kvd.KVD_ERR_RANGE, kvd.Plan, kvd.Pool(FAKE_SRC, big), kvd.Pool(far, big), 1, 8)
+    expect(kvd.KVD_ERR_RANGE, kvd.Plan, kvd.Pool(FAKE_SRC, big_bm), kvd.Pool(far, big), 1, 8)
+    kvd.Plan(kvd.Pool(FAKE_SRC, big_bm), kvd.Pool(far, big_bm), 1, 8).close()
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, kvd.Pool(FAKE_SRC, big_bm), kvd.Pool(far, big_bm), 1, 8, kvd.KVD_PLAN_PERSISTENT)
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, d, 1, 8, kvd.KVD_PLAN_WIDE_OFFSETS)                 # not block-major
     with pytest.raises(kvd.KvdError):
         kvd.kvd_plan_create(s.handle, 0, 1, 8)
 

@@ -518,10 +518,11 @@ def test_one_side_with_adjacent_k_and_v(adj_src, adj_dst):
 ], ids=["hm", "tm", "tm16-32", "hm32-8", "one-head"])
 @pytest.mark.parametrize("tokens", [333, 1024])
 @pytest.mark.parametrize("layers", [(0, 3), (1, 3), (1, 2)])
-def test_block_major_pools(gs, gd, tokens, layers):
+@pytest.mark.parametrize("flags", [0, kvd.KVD_PLAN_WIDE_OFFSETS], ids=["offsets32", "offsets48"])
+def test_block_major_pools(gs, gd, tokens, layers, flags):
     """Pools that keep all layers of a block together: what a request moves of a block is one byte range."""
     w = wl.Workload("block-major", gs, gd, [_frag_request(gs, gd, tokens, 41)], "bf16", 41, layers[0], layers[1])
-    x = G.run_and_compare(w, host_src(w))
+    x = G.run_and_compare(w, host_src(w), flags)
     got = x.plan.descriptors(x.stream.cuda_stream)
     assert np.array_equal(got, tl.oracle_plan_descriptors_block_major(w))
     st = x.plan.stats(x.stream.cuda_stream)
@@ -559,7 +560,7 @@ def test_block_major_batch_mixed_layer_ranges_and_baselines():
     want = wl.host_pool_sentinel(g)
     for r, (l0, l1) in zip(reqs, ranges):
         tl.oracle_pull_workload(wl.Workload("one", g, g, [r], "bf16", 0, l0, l1), src_host, want)
-    for flags in (0, kvd.KVD_PLAN_NO_COALESCE):
+    for flags in (0, kvd.KVD_PLAN_NO_COALESCE, kvd.KVD_PLAN_WIDE_OFFSETS):
         src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
         plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), len(reqs), 64, flags)
         plan.build_descriptors_batch([r.src_table for r in reqs[:3]], [r.dst_table for r in reqs[:3]], lens[:3], 0, 3)
@@ -568,7 +569,7 @@ def test_block_major_batch_mixed_layer_ranges_and_baselines():
         plan.pull()
         torch.cuda.synchronize()
         G.assert_bytes_equal(dst.cpu().numpy(), want, f"block-major batch, flags {flags}")
-        if flags == 0:
+        if flags != kvd.KVD_PLAN_NO_COALESCE:
             wb = wl.Workload("batch", g, g, reqs[:3], "bf16", 0)
             head = tl.oracle_plan_descriptors_block_major(wb)
             assert np.array_equal(plan.descriptors()[:len(head)], head)
@@ -710,6 +711,9 @@ def _random_case(seed):
     if seed >= 60:  # the later seeds also draw pools that keep all layers of a block together
         gs = dataclasses.replace(gs, block_major=bool(rng.random() < 0.6))
         gd = dataclasses.replace(gd, block_major=bool(rng.random() < 0.6))
+        foldable = gs.block_major and gd.block_major and (lay_s == lay_d or hk == 1)
+        if foldable and not (flags & kvd.KVD_PLAN_PERSISTENT) and rng.random() < 0.5:
+            flags |= kvd.KVD_PLAN_WIDE_OFFSETS
     return gs, gd, reqs, ranges, flags, batch
 
 
@@ -830,3 +834,72 @@ def test_full_config2_block_major_with_every_block_alone():
         got = dv[:, layer].permute(1, 0, 2).contiguous().view(torch.uint8).view(-1).cpu().numpy()
         G.assert_bytes_equal(got, G.oracle_expected(w1, src_host), f"{w.name} layer {layer}")
     x.close()
+
+
+def test_block_major_pools_above_64_gib():
+    """Two 66 GiB block-major pools: offsets beyond 2^32 sixteen-byte units, blocks that straddle the
+    32 GiB and 64 GiB marks, runs that cross them.  Bytes are checked through a compact renumbering of
+    the used blocks (the oracle never sees the pools); descriptors against the oracle's merged queue,
+    which the library may only differ from by splitting a run where it enters the next 32 GiB window."""
+    layers, hk, hd, tb = 3, 8, 128, 16
+    tile = tb * hk * hd * 2                       # 32 KiB
+    block = layers * 2 * tile                     # 192 KiB: does not divide 32 GiB
+    nb = 66 * 2**30 // block
+    g = wl.PoolGeometry(layers, nb, tb, hk, hd, 2, wl.BHTD, block_major=True)
+    assert g.total_bytes == 66 * 2**30
+    rng = np.random.default_rng(61)
+    m32, m64 = 2**35 // block, 2**36 // block     # the blocks that straddle the marks
+    assert m32 * block < 2**35 < (m32 + 1) * block and m64 * block < 2**36 < (m64 + 1) * block
+    # source: a run across the 64 GiB mark, one across the 32 GiB mark, lone blocks everywhere, the last block
+    st = np.concatenate([np.arange(m64 - 3, m64 + 4), np.arange(m32 - 2, m32 + 3),
+                         rng.choice(np.arange(m64 + 10, nb - 1), 40, replace=False), [nb - 1],
+                         rng.choice(np.arange(2000, m32 - 10), 40, replace=False), np.arange(1000, 1006)])
+    # destination: runs of the same lengths placed so that its marks fall at other positions of the runs
+    dt = np.concatenate([np.arange(m32 - 5, m32 + 2), np.arange(m64 - 1, m64 + 4),
+                         rng.choice(np.arange(m32 + 10, m64 - 10), 40, replace=False), [0],
+                         rng.choice(np.arange(m64 + 10, nb - 3000), 40, replace=False), np.arange(nb - 2000, nb - 1994)])
+    st, dt = st.astype(np.int32), dt.astype(np.int32)
+    assert len(set(st.tolist())) == len(st) == len(dt) == len(set(dt.tolist()))
+    seq = len(st) * tb - 5
+    say("allocating two 66 GiB pools")
+    src = G.device_random_pool(g, "bf16", 61)
+    dst = G.device_sentinel_pool(g)
+    w = wl.Workload("wide", g, g, [wl.Request(seq, st, dt)], "bf16", 61)
+    x = G.GpuTransfer(w, src, dst).run()
+    st_ = x.plan.stats(x.stream.cuda_stream)
+    say(f"{st_}")
+    assert st_["payload_bytes"] == seq * layers * 2 * hk * hd * 2
+    # descriptors: the oracle's queue merges the two long runs whole; the library splits each of them
+    # where the source or the destination enters the next 32 GiB window
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    want = tl.oracle_plan_descriptors_block_major(w)
+    assert got[:, 2].sum() == want[:, 2].sum() == st_["payload_bytes"]
+    pieces = []
+    for s0, d0, n in want.tolist():               # cut the oracle's transactions the same way
+        cuts = sorted({c - s0 for c in range(0, 2**37, 2**35) if s0 < c < s0 + n} |
+                      {c - d0 for c in range(0, 2**37, 2**35) if d0 < c < d0 + n})
+        # a cut falls on the first transaction (block piece) that STARTS in the new window
+        per_block = block                         # one transaction per whole block
+        cuts = sorted({-(-c // per_block) * per_block for c in cuts})
+        edges = [0] + [c for c in cuts if 0 < c < n] + [n]
+        pieces += [[s0 + a, d0 + a, b - a] for a, b in zip(edges[:-1], edges[1:])]
+    assert got.tolist() == pieces and len(got) > len(want)
+    # compact copies of the used blocks
+    us, ud = np.unique(st), np.unique(dt)
+    gs_c = wl.PoolGeometry(layers, len(us), tb, hk, hd, 2, wl.BHTD, block_major=True)
+    gd_c = wl.PoolGeometry(layers, len(ud), tb, hk, hd, 2, wl.BHTD, block_major=True)
+    s2 = src.view(torch.int16).view(nb, -1)
+    d2 = dst.view(torch.int16).view(nb, -1)
+    src_c = s2[torch.from_numpy(us.astype(np.int64)).cuda()].contiguous().cpu().numpy().view(np.uint8).reshape(-1)
+    got_c = d2[torch.from_numpy(ud.astype(np.int64)).cuda()].contiguous().cpu().numpy().view(np.uint8).reshape(-1)
+    wc = wl.Workload("compact", gs_c, gd_c, [wl.Request(seq, np.searchsorted(us, st).astype(np.int32),
+                                                        np.searchsorted(ud, dt).astype(np.int32))], "bf16", 61)
+    want_c = wl.host_pool_sentinel(gd_c)
+    tl.oracle_pull_workload(wc, src_c, want_c)
+    G.assert_bytes_equal(got_c, want_c, "compact view of the destination")
+    # nothing outside the used blocks was written
+    touched = sum(int((d2[b0:b0 + 32768] != wl.SENTINEL16).sum()) for b0 in range(0, nb, 32768))
+    assert touched == st_["payload_bytes"] // 2
+    x.close()
+    del src, dst, s2, d2
+    torch.cuda.empty_cache()
