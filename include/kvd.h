@@ -181,7 +181,8 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
  * moved, K and V.  seq_len == 0 appends nothing and succeeds.
  *
  * Address translation and coalescing run in a kernel enqueued on `stream`; kvd_pull must be
- * enqueued on the same stream (or be ordered after it by the caller).
+ * enqueued on the same stream (or be ordered after it by the caller).  `stream` must not be
+ * recording a HIP graph (KVD_ERR_INVALID): the host part of the call happens at once.
  *
  * Errors (checked on the host before anything is enqueued; the plan is unchanged on error):
  * KVD_ERR_INVALID (null, layer_begin >= layer_end), KVD_ERR_RANGE (block id outside its pool,
@@ -215,6 +216,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * lane.  When the plan's transactions are short (fewer than four work items each, as for lone
  * 4 KiB blocks) the first pull after an append is preceded by one small launch that groups the work
  * items by destination region.  May be called repeatedly; a plan with no requests is a no-op.
+ * May be recorded into a HIP graph (it allocates nothing and waits for nothing); the graph then
+ * replays the pull of the plan as it was built at recording time and must not be replayed after
+ * the plan has been reset or appended to.
  * Completion (section 4.1, Complete()) is the caller's synchronisation on `stream`.
  * Errors: KVD_ERR_INVALID, KVD_ERR_HIP, KVD_ERR_MISMATCH (KVD_PLAN_PERSISTENT with several layer
  * ranges in one plan).

@@ -919,6 +919,17 @@ void release_plan(kvd_plan *p)
     delete p;
 }
 
+// True while `stream` is recording a HIP graph (work enqueued now runs at replay, not now).
+bool is_capturing(void *stream)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)stream, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status == hipStreamCaptureStatusActive;
+}
+
 kvd_plan *as_plan(void *h)
 {
     kvd_plan *p = (kvd_plan *)h;
@@ -1098,6 +1109,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         return fail(KVD_ERR_RANGE, "layer range [%u, %u) outside a pool", layer_begin, layer_end);
     if (n_requests == 0) return KVD_OK;
     if (!src_tbls || !dst_tbls || !n_src || !n_dst || !seq_lens) return fail(KVD_ERR_INVALID, "null argument");
+    // the host part of a build (checks, table copies, the wait for the kernel's completion word)
+    // happens now, so its kernel cannot be deferred to a graph replay
+    if (is_capturing(stream)) return fail(KVD_ERR_INVALID, "kvd_build_descriptors cannot be recorded into a HIP graph");
     // with the layers folded into the block, this call's layer range sets how many planes a block has
     const uint32_t n_layers = layer_end - layer_begin;
     Geo folded = p->geo;
@@ -1286,11 +1300,14 @@ int kvd_pull(kvd_plan_t *p, void *stream)
         // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
         if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
             p->item_bound * a.slabs >= (1u << 17)) {
-            if (p->order_stale) {
+            // recorded into a graph, the ordering runs at every replay and the plan still counts
+            // as unordered for pulls outside the graph
+            const bool capturing = is_capturing(stream);
+            if (p->order_stale || capturing) {
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
                                    p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift, p->geo.wide);
                 KVD_HIP(hipGetLastError());
-                p->order_stale = false;
+                if (!capturing) p->order_stale = false;
             }
             a.items = p->ordered_dev;
         }

@@ -320,6 +320,45 @@ def test_region_ordering_of_short_scattered_transactions():
     x.close()
 
 
+@pytest.mark.parametrize("kind", ["runs", "short-scattered"])
+def test_pull_recorded_into_a_hip_graph(kind):
+    """kvd_pull inside a HIP graph: every replay moves the plan's bytes, also for plans whose work
+    items are grouped by region first; an eager pull between recording and the first replay is
+    right as well; builds refuse to be recorded."""
+    if kind == "runs":
+        w = wl.config2(num_layers=2, pool_blocks=2048, tokens=5000)
+    else:
+        g = wl.PoolGeometry(16, 65536, 16, 1, 8, 2, wl.BHTD)
+        rng = np.random.default_rng(43)
+        w = wl.Workload("graph-short", g, g, [wl.Request(4096 * 16 - 5, wl.scattered_table(rng, g.num_blocks, 4096),
+                                                         wl.scattered_table(rng, g.num_blocks, 4096))], "bf16", 43)
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, dst)
+    x.build()
+    x.stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=x.stream):
+        x.plan.pull(x.stream.cuda_stream)
+        with pytest.raises(kvd.KvdError):
+            r = w.requests[0]
+            x.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, 0, 1, x.stream.cuda_stream)
+    torch.cuda.synchronize()
+    assert int((dst.view(torch.int16) != wl.SENTINEL16).sum()) == 0     # recording moved nothing
+    x.pull()                                                             # eager, before any replay
+    x.stream.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "eager pull after recording")
+    for replay in range(3):
+        dst.view(torch.int16).fill_(wl.SENTINEL16)                       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"replay {replay}")
+    del graph
+    x.close()
+
+
 def test_many_transactions_and_one_long_run():
     # 16-byte rows, one head: 10000 lone blocks -> several passes of the coalescing workgroup
     g = wl.PoolGeometry(2, 20000, 16, 1, 8, 2, wl.BHTD)
