@@ -222,6 +222,32 @@ def main() -> int:
             per_layer()
             torch.cuda.synchronize()
             extras["per_layer_launches_total_us"] = (time.perf_counter() - t) * 1e6
+            # the same with ONE build for all layers and one kvd_pull_layers per layer, eagerly and as one HIP graph
+            x.plan.reset()
+            x.build(batch)
+
+            def per_layer_pulls():
+                for layer in layers:
+                    x.plan.pull_layers(layer, layer + 1, sh)
+            per_layer_pulls()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            x.plan.reset()
+            x.build(batch)
+            per_layer_pulls()
+            torch.cuda.synchronize()
+            extras["one_build_per_layer_pulls_total_us"] = (time.perf_counter() - t) * 1e6
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                per_layer_pulls()
+            graph.replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(5):
+                graph.replay()
+            torch.cuda.synchronize()
+            extras["per_layer_pulls_graph_replay_us"] = (time.perf_counter() - t) / 5 * 1e6
+            del graph
             ma = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
             mb = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
 

@@ -226,6 +226,19 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
 int kvd_pull(kvd_plan_t *plan, void *stream);
 
 /*
+ * The same as kvd_pull for layers [layer_begin, layer_end) of the pools only: of every request of
+ * the plan, the layers of that range that the request was built for are moved (none, if the ranges
+ * do not meet).  This is the layer-by-layer use that section 4.3 contrasts with the single shot: a
+ * prefill worker that has just written layer l issues kvd_pull_layers(plan, l, l + 1) against the
+ * plan built once for all layers, without another translation or coalescing pass.  Like kvd_pull it
+ * may be recorded into a HIP graph.
+ * Errors: KVD_ERR_INVALID (handle, empty range), KVD_ERR_RANGE (range outside a pool),
+ * KVD_ERR_MISMATCH (plan over block-major pools, whose descriptors span the layers; KVD_PLAN_PERSISTENT),
+ * KVD_ERR_HIP.
+ */
+int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, void *stream);
+
+/*
  * Reported baseline, not the product path: the buffer-based transfer the paper argues against
  * (section 4.1, message-based scheme).  Per iteration, as many 4 KiB work items of one (layer,
  * K/V) as `buffer_bytes` holds are gathered by a kernel into `send_buffer`, copied to

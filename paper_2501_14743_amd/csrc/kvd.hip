@@ -454,6 +454,10 @@ struct PullArgs {
     const Item *items;
     const Header *hdr;  // descriptor and work-item counts, written by the build kernel
     uint32_t slabs;     // (K, V slabs) * the largest layer count of any request
+    // 0: slab y of the grid is the y-th of each work item's own layers (the whole plan is moved);
+    // 1: slab y is layer `layer0 + y / (K, V slabs)` of the pools, and items without it sit out
+    uint32_t absolute_layers;
+    uint32_t layer0;
 };
 
 // Streaming 16-byte store: non-temporal at device scope.  Measured on MI355X, this cache policy
@@ -565,7 +569,13 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
     uint32_t piece;
     if (!pick_piece<T>(*a.hdr, blockIdx.x, &piece)) return;
     const Item it = a.items[piece / kParts];
-    move_unit(g, a, it, blockIdx.y, (piece % kParts) * T + threadIdx.x);
+    uint32_t y = blockIdx.y;
+    if (a.absolute_layers) {
+        const uint32_t rel = a.layer0 + (y >> g.kv_shift) - (it.layers & 0xFFFFu);  // wraps below the item's first layer
+        if (rel >= (it.layers >> 16)) return;
+        y = (rel << g.kv_shift) | (y & g.kv_shift);
+    }
+    move_unit(g, a, it, y, (piece % kParts) * T + threadIdx.x);
 }
 
 // Order of the work items for plans made of short, scattered descriptors (fewer than four work
@@ -1275,16 +1285,19 @@ int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
                                        layer_end, stream);
 }
 
-int kvd_pull(kvd_plan_t *p, void *stream)
+namespace {
+
+// The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
+int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
 {
-    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
-    if (p->reqs.empty()) return KVD_OK;
     PullArgs a;
     a.src_base = (const unsigned char *)p->src.base;
     a.dst_base = (unsigned char *)p->dst.base;
     a.items = p->items_dev;
     a.hdr = p->hdr_dev;
-    a.slabs = p->max_layers << p->geo.kv_shift;
+    a.slabs = (whole ? p->max_layers : l1 - l0) << p->geo.kv_shift;
+    a.absolute_layers = whole ? 0u : 1u;
+    a.layer0 = l0;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
         for (const ReqHost &r : p->reqs)
@@ -1299,7 +1312,7 @@ int kvd_pull(kvd_plan_t *p, void *stream)
         // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination
         // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
         if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
-            p->item_bound * a.slabs >= (1u << 17)) {
+            p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift) >= (1u << 17)) {
             // recorded into a graph, the ordering runs at every replay and the plan still counts
             // as unordered for pulls outside the graph
             const bool capturing = is_capturing(stream);
@@ -1321,6 +1334,29 @@ int kvd_pull(kvd_plan_t *p, void *stream)
     return KVD_OK;
 }
 
+}  // namespace
+
+int kvd_pull(kvd_plan_t *p, void *stream)
+{
+    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
+    if (p->reqs.empty()) return KVD_OK;
+    return launch_pull(p, stream, true, 0, 0);
+}
+
+int kvd_pull_layers(kvd_plan_t *p, uint32_t layer_begin, uint32_t layer_end, void *stream)
+{
+    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
+    if (layer_begin >= layer_end) return fail(KVD_ERR_INVALID, "empty layer range [%u, %u)", layer_begin, layer_end);
+    if (layer_end > p->src.num_layers || layer_end > p->dst.num_layers)
+        return fail(KVD_ERR_RANGE, "layer range [%u, %u) outside a pool", layer_begin, layer_end);
+    if (p->fold_layers)
+        return fail(KVD_ERR_MISMATCH, "plans over block-major pools move a block's layers as one range; build one plan "
+                                      "per layer range instead");
+    if (p->flags & KVD_PLAN_PERSISTENT) return fail(KVD_ERR_MISMATCH, "the persistent form moves whole plans only");
+    if (p->reqs.empty()) return KVD_OK;
+    return launch_pull(p, stream, false, layer_begin, layer_end);
+}
+
 int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_t buffer_bytes, void *stream)
 {
     if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
@@ -1338,6 +1374,8 @@ int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_
     a.items = p->items_dev;
     a.hdr = p->hdr_dev;
     a.slabs = p->max_layers << p->geo.kv_shift;
+    a.absolute_layers = 0;
+    a.layer0 = 0;
     const uint32_t cap = (uint32_t)std::min<uint64_t>(buffer_bytes / 4096, 1u << 20);
     for (uint32_t y = 0; y < a.slabs; ++y)
         for (uint32_t c0 = 0; c0 < h.n_items; c0 += cap) {

@@ -241,6 +241,66 @@ def test_layer_sub_range_and_mixed_ranges_in_one_plan():
     plan.close()
 
 
+@pytest.mark.parametrize("gs,gd", [(small_geom(num_layers=5), small_geom(num_layers=5)),
+                                   (small_geom(num_layers=5, kv_adjacent=True), small_geom(num_layers=5, kv_adjacent=True)),
+                                   (small_geom(num_layers=5), small_geom(num_layers=5, layout=wl.BTHD, block_tokens=32, num_blocks=48))],
+                         ids=["same", "kv-adjacent", "relayout"])
+def test_pull_layer_by_layer_from_one_plan(gs, gd):
+    """One plan, built once; its layers moved by separate kvd_pull_layers calls: after each call the
+    destination holds exactly the layers moved so far; requests built for other layers sit out."""
+    rng = np.random.default_rng(71)
+    free_s, free_d = np.ones(gs.num_blocks, bool), np.ones(gd.num_blocks, bool)
+    lens, ranges = [300, 77, 160], [(0, 5), (1, 3), (4, 5)]
+    reqs = [wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, gs.block_tokens), 4),
+                       wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, gd.block_tokens), 4)) for t in lens]
+    src_host = rng.integers(0, 256, size=gs.total_bytes, dtype=np.uint8)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(gd)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst.data_ptr(), gd), 3, 64)
+    for r, (l0, l1) in zip(reqs, ranges):
+        plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1)
+    want = wl.host_pool_sentinel(gd)
+    for (p0, p1) in [(2, 3), (0, 2), (3, 5)]:                           # out of order, two layers at a time too
+        plan.pull_layers(p0, p1)
+        torch.cuda.synchronize()
+        for r, (l0, l1) in zip(reqs, ranges):
+            a, b = max(l0, p0), min(l1, p1)
+            if a < b:
+                tl.oracle_pull_workload(wl.Workload("part", gs, gd, [r], "bf16", 0, a, b), src_host, want)
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"after layers [{p0}, {p1})")
+    with pytest.raises(kvd.KvdError):
+        plan.pull_layers(3, 6)
+    with pytest.raises(kvd.KvdError):
+        plan.pull_layers(2, 2)
+    plan.close()
+    g_bm = small_geom(block_major=True)
+    sp, dp = kvd.Pool(src.data_ptr(), g_bm), kvd.Pool(dst.data_ptr(), g_bm)
+    with pytest.raises(kvd.KvdError):
+        kvd.Plan(sp, dp, 1, 8).pull_layers(0, 1)
+
+
+def test_layer_by_layer_pulls_recorded_into_one_hip_graph():
+    """The launch-bound form of the transfer, one pull per layer, as one graph: each replay moves everything."""
+    w = wl.config2(num_layers=8, pool_blocks=1024, tokens=3000)
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, dst)
+    x.build()
+    x.stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=x.stream):
+        for layer in range(8):
+            x.plan.pull_layers(layer, layer + 1, x.stream.cuda_stream)
+    for replay in range(3):
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"replay {replay}")
+    del graph
+    x.close()
+
+
 def test_merge_across_requests_as_in_queue_example():
     # R1 reads block 0 into 5, R2 reads 1 into 6 (+ 3 into 9): first two merge (section 4.2)
     g = small_geom(num_layers=1)
