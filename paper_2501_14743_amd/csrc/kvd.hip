@@ -946,6 +946,53 @@ kvd_plan *as_plan(void *h)
     return (p && p->tag == kPlanTag) ? p : nullptr;
 }
 
+// The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
+int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
+{
+    PullArgs a;
+    a.src_base = (const unsigned char *)p->src.base;
+    a.dst_base = (unsigned char *)p->dst.base;
+    a.items = p->items_dev;
+    a.hdr = p->hdr_dev;
+    a.slabs = (whole ? p->max_layers : l1 - l0) << p->geo.kv_shift;
+    a.absolute_layers = whole ? 0u : 1u;
+    a.layer0 = l0;
+    constexpr int T = 64;
+    if (p->flags & KVD_PLAN_PERSISTENT) {
+        for (const ReqHost &r : p->reqs)
+            if (r.layer_begin != p->reqs[0].layer_begin || r.layer_end != p->reqs[0].layer_end)
+                return fail(KVD_ERR_MISMATCH, "the persistent form needs one layer range for the whole plan");
+        const uint32_t layers = p->fold_layers ? (1u << 16)
+                                               : (p->reqs[0].layer_begin | ((p->reqs[0].layer_end - p->reqs[0].layer_begin) << 16));
+        hipLaunchKernelGGL(kvd_pull_persistent_kernel, dim3((uint32_t)p->num_cus * 2), dim3(1024), 0,
+                           (hipStream_t)stream, p->geo, a, p->desc_dev, layers);
+    } else {
+        // transactions shorter than four work items on average (known on the host before merging):
+        // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination
+        // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
+        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
+            p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift) >= (1u << 17)) {
+            // recorded into a graph, the ordering runs at every replay and the plan still counts
+            // as unordered for pulls outside the graph
+            const bool capturing = is_capturing(stream);
+            if (p->order_stale || capturing) {
+                hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
+                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift, p->geo.wide);
+                KVD_HIP(hipGetLastError());
+                if (!capturing) p->order_stale = false;
+            }
+            a.items = p->ordered_dev;
+        }
+        // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
+        const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;
+        if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
+        hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, (hipStream_t)stream,
+                           p->geo, a);
+    }
+    KVD_HIP(hipGetLastError());
+    return KVD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1284,57 +1331,6 @@ int kvd_build_descriptors(kvd_plan_t *p, const int32_t *src_tbl, uint32_t n_src,
     return kvd_build_descriptors_batch(p, 1, &src_tbl, &n_src, &dst_tbl, &n_dst, &seq_len, layer_begin,
                                        layer_end, stream);
 }
-
-namespace {
-
-// The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
-int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
-{
-    PullArgs a;
-    a.src_base = (const unsigned char *)p->src.base;
-    a.dst_base = (unsigned char *)p->dst.base;
-    a.items = p->items_dev;
-    a.hdr = p->hdr_dev;
-    a.slabs = (whole ? p->max_layers : l1 - l0) << p->geo.kv_shift;
-    a.absolute_layers = whole ? 0u : 1u;
-    a.layer0 = l0;
-    constexpr int T = 64;
-    if (p->flags & KVD_PLAN_PERSISTENT) {
-        for (const ReqHost &r : p->reqs)
-            if (r.layer_begin != p->reqs[0].layer_begin || r.layer_end != p->reqs[0].layer_end)
-                return fail(KVD_ERR_MISMATCH, "the persistent form needs one layer range for the whole plan");
-        const uint32_t layers = p->fold_layers ? (1u << 16)
-                                               : (p->reqs[0].layer_begin | ((p->reqs[0].layer_end - p->reqs[0].layer_begin) << 16));
-        hipLaunchKernelGGL(kvd_pull_persistent_kernel, dim3((uint32_t)p->num_cus * 2), dim3(1024), 0,
-                           (hipStream_t)stream, p->geo, a, p->desc_dev, layers);
-    } else {
-        // transactions shorter than four work items on average (known on the host before merging):
-        // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination
-        // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
-        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
-            p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift) >= (1u << 17)) {
-            // recorded into a graph, the ordering runs at every replay and the plan still counts
-            // as unordered for pulls outside the graph
-            const bool capturing = is_capturing(stream);
-            if (p->order_stale || capturing) {
-                hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
-                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift, p->geo.wide);
-                KVD_HIP(hipGetLastError());
-                if (!capturing) p->order_stale = false;
-            }
-            a.items = p->ordered_dev;
-        }
-        // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
-        const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;
-        if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
-        hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, (hipStream_t)stream,
-                           p->geo, a);
-    }
-    KVD_HIP(hipGetLastError());
-    return KVD_OK;
-}
-
-}  // namespace
 
 int kvd_pull(kvd_plan_t *p, void *stream)
 {
