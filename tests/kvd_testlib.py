@@ -78,11 +78,21 @@ def oracle_plan_descriptors_block_major(w: wl.Workload) -> np.ndarray:
             t[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
             per_layer[layer] = t
         # where each piece's transactions end inside a layer's list: the list of the request cut
-        # after that piece is a prefix of the full list (pieces are enumerated independently)
-        ends = [len(orc.request_transactions(s_all[w.layer_begin], d_all[w.layer_begin], -1, r.src_table,
-                                             r.dst_table, min(t1, r.seq_len)))
-                for t1 in range(tmin, r.seq_len + tmin, tmin)]
-        assert ends[-1] == len(per_layer[w.layer_begin])
+        # after a piece is a prefix of the full list (pieces are enumerated independently), and
+        # every whole piece contributes as many transactions as the first one; a few cuts are
+        # taken from the oracle itself to make sure of that
+        first, total = w.layer_begin, len(per_layer[w.layer_begin])
+
+        def count_upto(t1):
+            return len(orc.request_transactions(s_all[first], d_all[first], -1, r.src_table, r.dst_table, min(t1, r.seq_len)))
+        n_whole = r.seq_len // tmin
+        per_piece = count_upto(tmin) if n_whole else 0
+        ends = [per_piece * (k + 1) for k in range(n_whole)]
+        if r.seq_len % tmin:
+            ends.append(total)
+        assert ends[-1] == total
+        for k in sorted({0, n_whole // 3, n_whole // 2, n_whole - 1} & set(range(n_whole))):
+            assert count_upto((k + 1) * tmin) == ends[k]
         lo = 0
         for hi in ends:
             for layer in range(w.layer_begin, w.layer_end):

@@ -634,6 +634,29 @@ def test_block_major_pools(gs, gd, tokens, layers, flags):
     x.close()
 
 
+@pytest.mark.parametrize("flags", [0, kvd.KVD_PLAN_WIDE_OFFSETS], ids=["offsets32", "offsets48"])
+def test_block_major_with_several_thousand_transactions(flags):
+    """More transactions than one pass of the build kernel takes (1024), in block-major pools: runs that
+    continue across the passes, two requests, the second one continuing the first one's last run."""
+    g = wl.PoolGeometry(2, 8192, 2, 2, 16, 2, wl.BHTD, block_major=True)     # 512-byte blocks
+    rng = np.random.default_rng(81)
+    free_s, free_d = np.ones(g.num_blocks, bool), np.ones(g.num_blocks, bool)
+    free_s[:40] = free_d[100:140] = False
+    n1 = 3300
+    r1 = wl.Request(n1 * 2, np.concatenate([wl.fragmented_allocation(rng, free_s, n1 - 20, 9), np.arange(0, 20)]).astype(np.int32),
+                    np.concatenate([wl.fragmented_allocation(rng, free_d, n1 - 20, 9), np.arange(100, 120)]).astype(np.int32))
+    r2 = wl.Request(1501 * 2 - 1, np.concatenate([np.arange(20, 40), wl.fragmented_allocation(rng, free_s, 1481, 9)]).astype(np.int32),
+                    np.concatenate([np.arange(120, 140), wl.fragmented_allocation(rng, free_d, 1481, 9)]).astype(np.int32))
+    w = wl.Workload("many-block-major", g, g, [r1, r2], "bf16", 81)
+    x = G.run_and_compare(w, host_src(w), flags)
+    got = x.plan.descriptors(x.stream.cuda_stream)
+    want = tl.oracle_plan_descriptors_block_major(w)
+    assert np.array_equal(got, want)
+    # the run 0..39 -> 100..139 crosses the two requests and is one descriptor
+    assert [0, 100 * 512, 40 * 512] in got.tolist()
+    x.close()
+
+
 @pytest.mark.parametrize("major_src,major_dst", [(True, False), (False, True)])
 def test_one_side_block_major(major_src, major_dst):
     """Only one pool keeps a block's layers together: nothing merges across layers, K and V still do."""
