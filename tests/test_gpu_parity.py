@@ -657,6 +657,42 @@ def test_block_major_with_several_thousand_transactions(flags):
     x.close()
 
 
+@pytest.mark.parametrize("gs,gd", [
+    (small_geom(block_major=True), small_geom(block_major=True, layout=wl.BTHD, block_tokens=32, num_blocks=48)),
+    (small_geom(block_major=True, layout=wl.BTHD, block_tokens=32, num_blocks=48), small_geom(block_major=True, block_tokens=8, num_blocks=192)),
+    (small_geom(block_major=True, layout=wl.BTHD), small_geom(block_major=True)),
+    (small_geom(block_major=True, num_kv_heads=3, head_dim=8, block_tokens=64, num_blocks=24),
+     small_geom(block_major=True, num_kv_heads=3, head_dim=8, layout=wl.BTHD, block_tokens=1, num_blocks=1536)),
+], ids=["ht16-th32", "th32-ht8", "th16-ht16", "ht64-th1"])
+def test_relayout_between_block_major_pools(gs, gd):
+    """Re-layout where both pools keep a block's layers together: pulled descriptor by descriptor.
+    A batch, a request with another layer range, then the same plan layer by layer."""
+    rng = np.random.default_rng(91)
+    free_s, free_d = np.ones(gs.num_blocks, bool), np.ones(gd.num_blocks, bool)
+    lens, ranges = [333, 64, 150], [(0, 3), (0, 3), (1, 2)]
+    reqs = [wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, gs.block_tokens), 4),
+                       wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, gd.block_tokens), 4)) for t in lens]
+    src_host = rng.integers(0, 256, size=gs.total_bytes, dtype=np.uint8)
+    want = wl.host_pool_sentinel(gd)
+    for r, (l0, l1) in zip(reqs, ranges):
+        tl.oracle_pull_workload(wl.Workload("one", gs, gd, [r], "bf16", 0, l0, l1), src_host, want)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(gd)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst.data_ptr(), gd), 3, 2048)
+    plan.build_descriptors_batch([r.src_table for r in reqs[:2]], [r.dst_table for r in reqs[:2]], lens[:2], 0, 3)
+    plan.build_descriptors(reqs[2].src_table, reqs[2].dst_table, lens[2], 1, 2)
+    assert plan.stats()["relayout"] == 1
+    plan.pull()
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "descriptor-by-descriptor pull")
+    dst.view(torch.int16).fill_(wl.SENTINEL16)
+    for layer in (2, 0, 1):
+        plan.pull_layers(layer, layer + 1)
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "the same, layer by layer")
+    G.assert_bytes_equal(src.cpu().numpy(), src_host, "source changed")
+    plan.close()
+
+
 @pytest.mark.parametrize("major_src,major_dst", [(True, False), (False, True)])
 def test_one_side_block_major(major_src, major_dst):
     """Only one pool keeps a block's layers together: nothing merges across layers, K and V still do."""
