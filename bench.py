@@ -270,17 +270,17 @@ def main() -> int:
             x.build(batch)
         # worst-case fragmentation (every block alone on both sides) of the same token count, in these pools and
         # in the same memory described as block-major pools ([block][layer][K/V]: one range per block over all layers)
-        if len(w.requests) == 1 and not stats["relayout"] and not w.src.block_major:
+        if len(w.requests) == 1 and not w.src.block_major:
             import dataclasses
             tokens = w.requests[0].seq_len
-            nblk = wl.blocks_for(tokens, w.src.block_tokens)
+            nblk_s, nblk_d = wl.blocks_for(tokens, w.src.block_tokens), wl.blocks_for(tokens, w.dst.block_tokens)
             for label, geo in (("lone_blocks", (w.src, w.dst)),
                                ("lone_blocks_block_major", (dataclasses.replace(w.src, block_major=True),
                                                             dataclasses.replace(w.dst, block_major=True)))):
                 rng = np.random.default_rng(w.seed + 3000)
                 wr = wl.Workload(f"{w.name}-{label}", geo[0], geo[1],
-                                 [wl.Request(tokens, wl.fixed_run_table(rng, geo[0].num_blocks, nblk, 1),
-                                             wl.fixed_run_table(rng, geo[1].num_blocks, nblk, 1))],
+                                 [wl.Request(tokens, wl.fixed_run_table(rng, geo[0].num_blocks, nblk_s, 1),
+                                             wl.fixed_run_table(rng, geo[1].num_blocks, nblk_d, 1))],
                                  w.dtype, w.seed, w.layer_begin, w.layer_end)
                 y = G.GpuTransfer(wr, src, dst, stream=stream)
                 y.build()
