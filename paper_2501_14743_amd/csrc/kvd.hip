@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     uint64_t prev_s = 0, prev_d = 0, prev_w = 0;
     if (n0 > 0 && !never_merge && a.may_merge_prev) {
         const Desc p = a.desc[n0 - 1];
-        const uint32_t hi = a.desc_hi[n0 - 1];
+        const uint32_t hi = g.wide ? a.desc_hi[n0 - 1] : 0u;
         const uint64_t s0 = ((uint64_t)(hi & 0xFFFFu) << 32) | p.src16, d0 = ((uint64_t)(hi >> 16) << 32) | p.dst16;
         have_prev = true;
         prev_s = s0 + (p.a - p.src16);
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             if (brk) {
                 a.desc[run].src16 = (uint32_t)t.s16;
                 a.desc[run].dst16 = (uint32_t)t.d16;
-                a.desc_hi[run] = (uint32_t)(t.s16 >> 32) | ((uint32_t)(t.d16 >> 32) << 16);
+                if (g.wide) a.desc_hi[run] = (uint32_t)(t.s16 >> 32) | ((uint32_t)(t.d16 >> 32) << 16);
                 if (relayout) a.desc[run].a = t.meta;
             }
             // the last member of a descriptor (so far) records where it ends; a later tile or
@@ -355,8 +355,11 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     }
 
     // The host's block tables and request list are not read again: tell the host, which may then
-    // overwrite them for the next build while this one is still running.
-    if (tid == 0) __hip_atomic_store(a.done, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    // overwrite them for the next build while this one is still running.  Every lane has used what
+    // it loaded from them before the barrier that ends the loop above, so the loads are complete;
+    // nothing is published to the host with this word, hence no release (which would write the
+    // L2 back first).
+    if (tid == 0) __hip_atomic_store(a.done, a.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 
     // work-item prefix over the descriptors that are new or were extended
     const uint32_t n1 = runs;
@@ -411,7 +414,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             }
             const Desc d = a.desc[w0 + lo];
             const uint32_t cl = c - d.prefix;
-            const Item it = make_item(g, d, a.desc_hi[w0 + lo], cl, a.layers);
+            const Item it = make_item(g, d, g.wide ? a.desc_hi[w0 + lo] : 0u, cl, a.layers);
             a.items[c] = it;
         }
         __syncthreads();
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc
         if (desc[mid].prefix <= c) lo = mid; else hi = mid;
     }
     const Desc d = desc[lo];
-    items[c] = make_item(g, d, desc_hi[lo], c - d.prefix, layers);
+    items[c] = make_item(g, d, g.wide ? desc_hi[lo] : 0u, c - d.prefix, layers);
 }
 
 // ------------------------------------------------------------------ pull
@@ -810,7 +813,7 @@ struct kvd_plan {
     int32_t *tables_src_dev, *tables_dst_dev;
     ReqDev *reqs_pinned, *reqs_pinned_dev;  // one entry per request, same kind of memory
     Desc *desc_dev;
-    uint32_t *desc_hi_dev;  // upper halves of the descriptors' offsets (zero unless geo.wide)
+    uint32_t *desc_hi_dev;  // upper halves of the descriptors' offsets (used only when geo.wide)
     Item *items_dev;
     Item *ordered_dev;     // items grouped by destination region (plans of short descriptors)
     bool order_stale;      // requests were appended since ordered_dev was last written
@@ -1518,7 +1521,8 @@ int kvd_plan_get_descriptors(kvd_plan_t *p, void *stream, kvd_span_t *spans, kvd
     std::vector<Desc> d(h.n_desc);
     std::vector<uint32_t> hi(h.n_desc);
     KVD_HIP(hipMemcpy(d.data(), p->desc_dev, (size_t)h.n_desc * sizeof(Desc), hipMemcpyDeviceToHost));
-    KVD_HIP(hipMemcpy(hi.data(), p->desc_hi_dev, (size_t)h.n_desc * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    if (p->geo.wide)  // written only for plans with 48-bit offsets
+        KVD_HIP(hipMemcpy(hi.data(), p->desc_hi_dev, (size_t)h.n_desc * sizeof(uint32_t), hipMemcpyDeviceToHost));
     for (uint32_t i = 0; i < h.n_desc && i < cap; ++i) {
         if (relayout) {
             pieces[i].src_block = (int32_t)(d[i].src16 / p->geo.src_block16);
