@@ -791,6 +791,19 @@ def test_largest_block_size(gs, gd):
     G.run_and_compare(w, host_src(w)).close()
 
 
+@pytest.mark.parametrize("row_units", [256, 255, 129, 128, 86])
+@pytest.mark.parametrize("lay_s,lay_d,tb_d", [(wl.BHTD, wl.BHTD, 4), (wl.BTHD, wl.BTHD, 8), (wl.BHTD, wl.BTHD, 8),
+                                               (wl.BTHD, wl.BHTD, 2)])
+def test_widest_rows(row_units, lay_s, lay_d, tb_d):
+    """(token, head) rows up to the limit of 4096 bytes: one row per work item, rows that do not
+    divide a work item, re-layout with a single row per item."""
+    hd = row_units * 16 // 2
+    gs = wl.PoolGeometry(2, 40, 4, 3, hd, 2, lay_s)
+    gd = wl.PoolGeometry(2, 4 * 40 // tb_d + 2, tb_d, 3, hd, 2, lay_d)
+    w = one_request(gs, gd, 4 * 31 + 3, seed=row_units)
+    G.run_and_compare(w, host_src(w)).close()
+
+
 def test_slab_larger_than_4_gib():
     """Block offsets beyond 2^32 bytes inside one (layer, K/V) slab; checked through a compact
     renumbering of the blocks that are used (the oracle never sees the 10 GiB pools)."""
