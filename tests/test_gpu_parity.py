@@ -804,6 +804,16 @@ def test_widest_rows(row_units, lay_s, lay_d, tb_d):
     G.run_and_compare(w, host_src(w)).close()
 
 
+@pytest.mark.parametrize("block_major", [False, True])
+def test_many_layers(block_major):
+    """Several hundred layers: as many slabs in the grid, or one folded range per block of 600 planes."""
+    g = wl.PoolGeometry(300, 24, 4, 1, 8, 2, wl.BHTD, block_major=block_major)
+    w = one_request(g, g, 4 * 9 + 1, seed=300)
+    G.run_and_compare(w, host_src(w)).close()
+    w2 = one_request(g, g, 4 * 9 + 1, seed=301, layer_begin=257, layer_end=300)
+    G.run_and_compare(w2, host_src(w2)).close()
+
+
 def test_slab_larger_than_4_gib():
     """Block offsets beyond 2^32 bytes inside one (layer, K/V) slab; checked through a compact
     renumbering of the blocks that are used (the oracle never sees the 10 GiB pools)."""
