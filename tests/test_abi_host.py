@@ -238,3 +238,12 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(kvd, "LIB_PATH", "/nonexistent/libkvd.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         kvd.kvd_pull(1)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU benchmark: with --gpus above 1 it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
