@@ -33,6 +33,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <thread>
 #include <vector>
 
 #include "kvd.h"
@@ -943,6 +944,7 @@ int wait_for_builds(kvd_plan *p)
     for (uint32_t spins = 1;; ++spins) {
         if (*done == p->build_seq) return KVD_OK;
         __builtin_ia32_pause();
+        if (spins > 4096) std::this_thread::yield();  // a long pull is ahead of the build: let other threads run
         if ((spins & 0xFFF) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) break;
     }
     KVD_HIP(hipStreamSynchronize(p->build_stream));
