@@ -905,9 +905,29 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *it
     }
 }
 
-int ensure_allocated(kvd_plan *p)
+// Frees whatever of the plan's scratch exists (pointers are null until allocated).
+void free_scratch(kvd_plan *p)
 {
-    if (p->allocated) return KVD_OK;
+    if (p->done_host) (void)hipHostFree(p->done_host);
+    if (p->tables_src) (void)hipHostFree(p->tables_src);
+    if (p->tables_dst) (void)hipHostFree(p->tables_dst);
+    if (p->reqs_pinned) (void)hipHostFree(p->reqs_pinned);
+    if (p->desc_dev) (void)hipFree(p->desc_dev);
+    if (p->desc_hi_dev) (void)hipFree(p->desc_hi_dev);
+    if (p->items_dev) (void)hipFree(p->items_dev);
+    if (p->ordered_dev) (void)hipFree(p->ordered_dev);
+    if (p->hdr_dev) (void)hipFree(p->hdr_dev);
+    p->done_host = nullptr;
+    p->tables_src = p->tables_dst = nullptr;
+    p->reqs_pinned = nullptr;
+    p->desc_dev = nullptr;
+    p->desc_hi_dev = nullptr;
+    p->items_dev = p->ordered_dev = nullptr;
+    p->hdr_dev = nullptr;
+}
+
+int allocate_scratch(kvd_plan *p)
+{
     KVD_HIP(hipGetDevice(&p->device));
     hipDeviceProp_t prop;
     KVD_HIP(hipGetDeviceProperties(&prop, p->device));
@@ -929,6 +949,18 @@ int ensure_allocated(kvd_plan *p)
     *p->done_host = 0;
     p->build_seq = 0;
     p->build_stream = nullptr;
+    return KVD_OK;
+}
+
+// The plan's scratch, allocated at the first build that passes validation; all or nothing.
+int ensure_allocated(kvd_plan *p)
+{
+    if (p->allocated) return KVD_OK;
+    const int rc = allocate_scratch(p);
+    if (rc != KVD_OK) {
+        free_scratch(p);  // keeps the message of the failed call
+        return rc;
+    }
     p->allocated = true;
     return KVD_OK;
 }
@@ -956,15 +988,7 @@ void release_plan(kvd_plan *p)
 {
     if (p->allocated) {
         (void)wait_for_builds(p);
-        (void)hipHostFree(p->done_host);
-        (void)hipHostFree(p->tables_src);
-        (void)hipHostFree(p->tables_dst);
-        (void)hipHostFree(p->reqs_pinned);
-        (void)hipFree(p->desc_dev);
-        (void)hipFree(p->desc_hi_dev);
-        (void)hipFree(p->items_dev);
-        (void)hipFree(p->ordered_dev);
-        (void)hipFree(p->hdr_dev);
+        free_scratch(p);
     }
     p->tag = 0;
     delete p;
