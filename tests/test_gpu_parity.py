@@ -521,6 +521,44 @@ def test_plan_reuse_reset_repeat_and_round_trip():
     y.close()
 
 
+@pytest.mark.parametrize("block_major", [False, True])
+def test_one_plan_reused_for_a_hundred_random_batches(block_major):
+    """reset / build / pull on one plan object a hundred times with different requests each time
+    (single calls, batches, appended requests with other layer ranges); the destination pool, which
+    keeps what earlier rounds wrote, is compared with the oracle's after every round."""
+    g = wl.PoolGeometry(3, 512, 16, 2, 64, 2, wl.BHTD, block_major=block_major)
+    rng = np.random.default_rng(1234)
+    src_host = rng.integers(0, 256, size=g.total_bytes, dtype=np.uint8)
+    want = wl.host_pool_sentinel(g)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    sh = stream.cuda_stream
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), g), kvd.Pool(dst.data_ptr(), g), 4, 512)
+    for it in range(100):
+        plan.reset()
+        free_s, free_d = np.ones(512, bool), np.ones(512, bool)
+        n_req = int(rng.integers(1, 5))
+        lens = [int(rng.integers(1, 1800)) for _ in range(n_req)]
+        reqs = [wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, 16), 6),
+                           wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, 16), 6)) for t in lens]
+        if rng.random() < 0.5:
+            ranges = [(0, 3)] * n_req
+            plan.build_descriptors_batch([r.src_table for r in reqs], [r.dst_table for r in reqs], lens, 0, 3, sh)
+        else:
+            ranges = []
+            for r in reqs:
+                l0 = int(rng.integers(0, 3))
+                ranges.append((l0, int(rng.integers(l0 + 1, 4))))
+                plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, ranges[-1][0], ranges[-1][1], sh)
+        plan.pull(sh)
+        for r, (l0, l1) in zip(reqs, ranges):
+            tl.oracle_pull_workload(wl.Workload("one", g, g, [r], "bf16", 0, l0, l1), src_host, want)
+        stream.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"round {it}")
+    plan.close()
+
+
 def test_blockwise_memcpy_baseline_gives_the_same_bytes():
     w = wl.config2(num_layers=2, pool_blocks=512, tokens=1000)
     src_host = host_src(w)
