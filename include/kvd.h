@@ -215,7 +215,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * most 4 KiB and each (work item, layer, K/V) is moved by its own small workgroup, 16 bytes per
  * lane.  When the plan's transactions are short (fewer than four work items each, as for lone
  * 4 KiB blocks) the first pull after an append is preceded by one small launch that groups the work
- * items by destination region.  May be called repeatedly; a plan with no requests is a no-op.
+ * items by destination region; re-layout plans between two pools whose blocks are the outermost
+ * axis are walked block by block (all slabs of a block together) instead of slab by slab.  May be
+ * called repeatedly; a plan with no requests is a no-op.
  * May be recorded into a HIP graph (it allocates nothing and waits for nothing); the graph then
  * replays the pull of the plan as it was built at recording time and must not be replayed after
  * the plan has been reset or appended to.
