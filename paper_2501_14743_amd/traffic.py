@@ -29,12 +29,13 @@ HOST_MARKER = "// --------------------------------------------------------------
 
 def source_hash() -> str:
     """sha256 of the device part of the source (everything above the host-side marker: structures
-    and kernels) with comments and white space removed, so that only a change of the kernels'
+    and kernels) with #include lines, comments and white space removed, so that only a change of the kernels'
     code invalidates a recorded measurement."""
     with open(SOURCE) as f:
         text = f.read()
     assert HOST_MARKER in text, "host-side marker missing from the kernel source"
     text = text[:text.index(HOST_MARKER)]
+    text = re.sub(r"^\s*#\s*include[^\n]*$", "", text, flags=re.M)  # host headers come and go
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"//[^\n]*", "", text)
     text = re.sub(r"\s+", "", text)
