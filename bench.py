@@ -79,6 +79,9 @@ def main() -> int:
     ap.add_argument("--run-length-sweep", action="store_true",
                     help="also time the pull of the same token count with block tables made of runs of exactly "
                          "1, 2, 4, ... consecutive blocks (both sides, source only, destination only)")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="also time the pull of 1/8 ... 2x the configuration's token count (configurations 2 and 4), "
+                         "the bandwidth-against-transfer-size curve of the paper's motivation")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
@@ -291,6 +294,37 @@ def main() -> int:
                 y.plan.pull(sh)
                 extras[f"{label}_pull_us"] = timed(lambda: y.plan.pull(sh), 10)
                 y.close()
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
+        # bandwidth against the size of the transfer: the same recipe for the block tables, other token counts
+        if args.size_sweep and args.config in (2, 4):
+            sweep = {}
+            tokens0 = w.requests[0].seq_len
+            for tokens in [tokens0 // 8, tokens0 // 4, tokens0 // 2, tokens0, 2 * tokens0]:
+                if wl.blocks_for(tokens, w.src.block_tokens) * 2 > w.src.num_blocks:
+                    continue
+                ws = wl.CONFIGS[args.config](tokens=tokens)
+                y = G.GpuTransfer(ws, src, dst, stream=stream)
+                y.build()
+                y.plan.pull(sh)
+                us = timed(lambda: y.plan.pull(sh), 10)
+                p_bytes = y.plan.stats(sh)["payload_bytes"]
+                groups = []  # best of three groups of ten steps: the HIP runtime stalls once, for tens of
+                for _ in range(3):  # milliseconds, after some five hundred launches of a process
+                    t_step = time.perf_counter()
+                    for _ in range(10):
+                        y.plan.reset()
+                        y.build()
+                        y.plan.pull(sh)
+                    torch.cuda.synchronize()
+                    groups.append((time.perf_counter() - t_step) / 10 * 1e6)
+                step_us = min(groups)
+                sweep[str(tokens)] = {"payload_bytes": p_bytes, "pull_us": us, "pct_of_peak": 2 * p_bytes / us / 1e3 / PEAK_HBM_GBPS * 100,
+                                      "step_us": step_us, "step_pct_of_peak": 2 * p_bytes / step_us / 1e3 / PEAK_HBM_GBPS * 100}
+                y.close()
+            extras["size_sweep"] = sweep
             x.plan.reset()
             x.build(batch)
             x.plan.pull(sh)
