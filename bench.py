@@ -121,8 +121,6 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    stats = x.plan.stats(sh)
-    payload = stats["payload_bytes"]
     stride = max(1, args.event_stride)
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(0, args.steps, stride)]
@@ -132,6 +130,8 @@ def main() -> int:
         step(events[i // stride] if i % stride == 0 else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    stats = x.plan.stats(sh)  # of the last step's plan
+    payload = stats["payload_bytes"]
     pull_ms = np.array([a.elapsed_time(b) for a, b in events])
     ms_per_step = elapsed / args.steps * 1e3
     value = 2 * payload * args.steps / elapsed / 1e9
