@@ -15,7 +15,8 @@
  *                  queued ranges are coalesced (section 4.2);
  *                  kvd_pull : every (merged or unmerged) range is issued at once, no waiting
  *                  in between.
- *   Complete()  -> the caller's stream order / event after kvd_pull.
+ *   Complete()  -> the caller's stream order / event after kvd_pull, or kvd_complete: a word in
+ *                  memory that names the finished request.
  *
  * Conventions
  *   - Every call returns KVD_OK (0) or a negative kvd_status_t; kvd_last_error() gives a
@@ -239,6 +240,17 @@ int kvd_pull(kvd_plan_t *plan, void *stream);
  * KVD_ERR_HIP.
  */
 int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, void *stream);
+
+/*
+ * Complete() of section 4.1 as the paper sends it, a message naming the finished request: stores
+ * `value` (a request id, a sequence number) into *flag once everything enqueued on `stream`
+ * before this call - the pulls - has finished, with the pulled bytes visible to any reader of the
+ * flag first.  `flag` is 8-byte aligned and owned by the caller: device memory, or pinned host
+ * memory (its host address) that a CPU thread polls; anything else is refused.  A caller that synchronises the stream or
+ * records an event itself does not need this call.  May be recorded into a HIP graph.
+ * Errors: KVD_ERR_INVALID (null or misaligned flag, memory the GPU cannot reach), KVD_ERR_HIP.
+ */
+int kvd_complete(uint64_t *flag, uint64_t value, void *stream);
 
 /*
  * Reported baseline, not the product path: the buffer-based transfer the paper argues against

@@ -735,6 +735,14 @@ __global__ __launch_bounds__(1024) void kvd_pull_persistent_kernel(Geo g, PullAr
     }
 }
 
+// Complete() of section 4.1 as a message in memory: one word that says which request is done.
+// Stream order puts it behind the pulls; the release at system scope makes their writes visible
+// to whoever reads the word (another GPU, the host) before the word itself.
+__global__ void kvd_complete_kernel(uint64_t *flag, uint64_t value)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ __launch_bounds__(256) void kvd_copy_kernel(u32x4 *__restrict__ dst,
                                                        const u32x4 *__restrict__ src, uint64_t units)
 {
@@ -1430,6 +1438,22 @@ int kvd_pull_layers(kvd_plan_t *p, uint32_t layer_begin, uint32_t layer_end, voi
     if (p->flags & KVD_PLAN_PERSISTENT) return fail(KVD_ERR_MISMATCH, "the persistent form moves whole plans only");
     if (p->reqs.empty()) return KVD_OK;
     return launch_pull(p, stream, false, layer_begin, layer_end);
+}
+
+int kvd_complete(uint64_t *flag, uint64_t value, void *stream)
+{
+    if (!flag) return fail(KVD_ERR_INVALID, "null flag");
+    if ((uintptr_t)flag % 8) return fail(KVD_ERR_INVALID, "flag must be 8-byte aligned");
+    // the kernel must be able to reach the word: device memory, or pinned host memory that is mapped
+    hipPointerAttribute_t at;
+    if (hipPointerGetAttributes(&at, flag) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KVD_ERR_INVALID, "flag is not memory the GPU can reach (device memory or pinned host memory)");
+    }
+    if (!at.devicePointer) return fail(KVD_ERR_INVALID, "flag is host memory that is not mapped into the device");
+    hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (uint64_t *)at.devicePointer, value);
+    KVD_HIP(hipGetLastError());
+    return KVD_OK;
 }
 
 int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_t buffer_bytes, void *stream)

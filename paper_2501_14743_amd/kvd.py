@@ -87,6 +87,7 @@ def lib() -> ctypes.CDLL:
                                               u32, u32, vp]
     L.kvd_pull.argtypes = [vp, vp]
     L.kvd_pull_layers.argtypes = [vp, u32, u32, vp]
+    L.kvd_complete.argtypes = [vp, u64, vp]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
     L.kvd_pull_staged.argtypes = [vp, vp, vp, u64, vp]
     L.kvd_plan_reset.argtypes = [vp]
@@ -97,7 +98,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
-                 "kvd_pull_layers",
+                 "kvd_pull_layers", "kvd_complete",
                  "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain"):
         getattr(L, name).restype = ctypes.c_int
@@ -167,6 +168,10 @@ def kvd_pull(plan: int, stream: int = 0) -> None:
 
 def kvd_pull_layers(plan: int, layer_begin: int, layer_end: int, stream: int = 0) -> None:
     _check(lib().kvd_pull_layers(plan, layer_begin, layer_end, stream))
+
+
+def kvd_complete(flag_ptr: int, value: int, stream: int = 0) -> None:
+    _check(lib().kvd_complete(flag_ptr, value, stream))
 
 
 def kvd_pull_blockwise_memcpy(plan: int, stream: int = 0) -> None:

@@ -301,6 +301,44 @@ def test_layer_by_layer_pulls_recorded_into_one_hip_graph():
     x.close()
 
 
+def test_completion_word():
+    """kvd_complete behind a pull: once the word shows the request id, the pulled bytes are there -
+    read by the host from pinned memory without synchronising the stream, and from device memory."""
+    w = wl.config2(num_layers=4, pool_blocks=2048, tokens=8192)
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    pinned = torch.zeros(2, dtype=torch.int64).pin_memory()
+    on_device = torch.zeros(1, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    x = G.GpuTransfer(w, src, dst)
+    sh = x.stream.cuda_stream
+    for request_id in (41, 42):
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        x.after_torch()
+        x.plan.reset()
+        x.build()
+        x.pull()
+        kvd.kvd_complete(pinned.data_ptr(), request_id, sh)
+        kvd.kvd_complete(on_device.data_ptr(), request_id + 100, sh)
+        peer = torch.cuda.Stream()              # a reader that synchronises with nothing but the word
+        import time
+        t0 = time.time()
+        while int(pinned[0]) != request_id:
+            assert time.time() - t0 < 20, "the completion word never arrived"
+        with torch.cuda.stream(peer):
+            got = dst.clone()
+        peer.synchronize()
+        G.assert_bytes_equal(got.cpu().numpy(), want, f"after completion word {request_id}")
+        x.stream.synchronize()
+        assert int(on_device[0]) == request_id + 100
+    host_only = np.zeros(1, np.int64)
+    for bad in (0, pinned.data_ptr() + 4, host_only.ctypes.data):
+        with pytest.raises(kvd.KvdError):
+            kvd.kvd_complete(bad, 1, sh)
+    x.close()
+
+
 def test_merge_across_requests_as_in_queue_example():
     # R1 reads block 0 into 5, R2 reads 1 into 6 (+ 3 into 9): first two merge (section 4.2)
     g = small_geom(num_layers=1)
