@@ -1,4 +1,4 @@
-"""Builds libkvd.so (HIP kernels + C ABI) in-tree for gfx950 with hipcc."""
+"""Builds libkvd.so (csrc/kvd.hip, which includes csrc/kvd_kernels.h: HIP kernels + C ABI) in-tree for gfx950 with hipcc."""
 from __future__ import annotations
 
 import os

@@ -19,22 +19,16 @@ import re
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
-SOURCE = os.path.join(PKG, "csrc", "kvd.hip")
+SOURCE = os.path.join(PKG, "csrc", "kvd_kernels.h")
 RECORD = os.path.join(PKG, "hbm_traffic.json")
 COPY_BYTES = 1 << 30
 
 
-HOST_MARKER = "// ------------------------------------------------------------------ host side"
-
-
 def source_hash() -> str:
-    """sha256 of the device part of the source (everything above the host-side marker: structures
-    and kernels) with #include lines, comments and white space removed, so that only a change of the kernels'
-    code invalidates a recorded measurement."""
+    """sha256 of the kernel source (structures and device code) with #include lines, comments and
+    white space removed, so that only a change of the kernels' code invalidates a recorded measurement."""
     with open(SOURCE) as f:
         text = f.read()
-    assert HOST_MARKER in text, "host-side marker missing from the kernel source"
-    text = text[:text.index(HOST_MARKER)]
     text = re.sub(r"^\s*#\s*include[^\n]*$", "", text, flags=re.M)  # host headers come and go
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"//[^\n]*", "", text)
