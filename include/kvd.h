@@ -242,6 +242,35 @@ int kvd_pull(kvd_plan_t *plan, void *stream);
 int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, void *stream);
 
 /*
+ * For callers that cannot allocate device memory - code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: kvd_build_descriptors + kvd_pull for ONE request in one
+ * call that allocates nothing, on the device or through any allocating runtime routine.  The pools
+ * are described by their metadata directly (no handles), the block tables are HOST arrays as for
+ * kvd_build_descriptors (they travel in kernel arguments, 448 ids per side and launch), and what a
+ * plan keeps in allocated scratch lives in one array of about 18.6 MiB that is part of the library's
+ * code object and that every GPU the call is used on holds until the process ends.
+ * Limits (KVD_ERR_CAPACITY, nothing is enqueued): at most KVD_NOALLOC_MAX_BLOCKS block-table
+ * entries per side, 2^17 read transactions before merging and KVD_NOALLOC_MAX_WORK_ITEMS work items
+ * of 4 KiB (per (layer, K/V); for block-major pools over all layers of the request).
+ * `flags`: KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS, KVD_PLAN_QUEUE_ORDER or 0; anything else is
+ * KVD_ERR_INVALID.  Moves exactly the bytes that kvd_plan_create(flags) + kvd_build_descriptors +
+ * kvd_pull move for the same arguments, with the same kernels, enqueued on `stream`; may be
+ * recorded into a HIP graph (the tables are captured by value).  seq_len == 0 enqueues nothing.
+ * All calls on one GPU share that GPU's array: a call may follow another on the same stream, but
+ * calls whose kernels could overlap on one GPU (different streams without ordering between them,
+ * different threads) race and give undefined destination bytes.  The array needs no clearing
+ * between calls: every part that is read is written first by the same call.
+ * Errors: as kvd_pool_create, kvd_plan_create and kvd_build_descriptors for the same arguments,
+ * all detected on the host before anything is enqueued.
+ */
+#define KVD_NOALLOC_MAX_BLOCKS 8192u
+#define KVD_NOALLOC_MAX_WORK_ITEMS (1u << 19)
+int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst,
+                     const int32_t *src_block_table, uint32_t n_src,
+                     const int32_t *dst_block_table, uint32_t n_dst, uint32_t seq_len,
+                     uint32_t layer_begin, uint32_t layer_end, uint32_t flags, void *stream);
+
+/*
  * Complete() of section 4.1 as the paper sends it, a message naming the finished request: stores
  * `value` (a request id, a sequence number) into *flag once everything enqueued on `stream`
  * before this call - the pulls - has finished, with the pulled bytes visible to any reader of the

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -343,36 +344,41 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     return KVD_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-const char *kvd_last_error(void) { return g_err; }
-
-int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out)
+// What every launch of the build kernel takes from the plan: where its scratch is, the layer range,
+// the sizes of the batch.  The caller adds the batch itself (reqs, first, n_req) and how it joins
+// the queue (fresh, may_merge_prev).
+BuildArgs build_args(kvd_plan *p, const Geo &g, uint32_t layer_begin, uint32_t n_layers, uint32_t batch_txn,
+                     uint32_t batch_items)
 {
-    if (!desc || !out) return fail(KVD_ERR_INVALID, "null argument");
-    *out = nullptr;
-    uint64_t extent = 0;
-    int rc = check_pool_desc(*desc, &extent);
-    if (rc != KVD_OK) return rc;
-    kvd_pool *p = new (std::nothrow) kvd_pool;
-    if (!p) return fail(KVD_ERR_INVALID, "out of host memory");
-    p->tag = kPoolTag;
-    p->d = *desc;
-    p->extent_bytes = extent;
-    *out = p;
-    return KVD_OK;
+    BuildArgs a{};
+    a.tables_src = p->tables_src_dev;
+    a.tables_dst = p->tables_dst_dev;
+    a.reqs = nullptr;
+    a.desc = p->desc_dev;
+    a.desc_hi = p->desc_hi_dev;
+    a.items = p->items_dev;
+    a.hdr = p->hdr_dev;
+    a.n_req = 1;
+    a.base_src16 = p->fold_layers ? (uint32_t)(layer_begin * g.src_layer_bytes / kUnitBytes) : 0u;
+    a.base_dst16 = p->fold_layers ? (uint32_t)(layer_begin * g.dst_layer_bytes / kUnitBytes) : 0u;
+    a.n_txn = batch_txn;
+    a.layers = p->fold_layers ? (1u << 16) : (layer_begin | (n_layers << 16));
+    a.fresh = 1;
+    a.may_merge_prev = 0;
+    a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
+    a.expand_inline = batch_items <= kInlineItems ? 1u : 0u;
+    a.done = p->done_dev;
+    a.seq = ++p->build_seq;
+    return a;
 }
 
-int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_requests,
-                    uint32_t max_total_blocks, uint32_t flags, kvd_plan_t **out)
+// Everything of a plan that follows from the two pools' metadata and the flags: the geometry the
+// kernels take, which axes fold into one byte range, capacity bounds.  Allocates nothing and leaves
+// the plan's bookkeeping and scratch pointers alone.
+int init_plan(kvd_plan *p, const kvd_pool_desc_t &s, uint64_t src_extent, const kvd_pool_desc_t &d, uint64_t dst_extent,
+              uint32_t max_requests, uint32_t max_total_blocks, uint32_t flags)
 {
-    if (!src || !dst || !out) return fail(KVD_ERR_INVALID, "null argument");
-    *out = nullptr;
-    if (src->tag != kPoolTag || dst->tag != kPoolTag) return fail(KVD_ERR_INVALID, "not a pool handle");
     if (!max_requests || !max_total_blocks) return fail(KVD_ERR_INVALID, "zero capacity");
-    const kvd_pool_desc_t &s = src->d, &d = dst->d;
     if (s.num_kv_heads != d.num_kv_heads || s.head_dim != d.head_dim || s.elem_bytes != d.elem_bytes)
         return fail(KVD_ERR_MISMATCH, "pools differ in num_kv_heads, head_dim or elem_bytes");
     const uint32_t tmin = std::min(s.block_tokens, d.block_tokens);
@@ -381,12 +387,8 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
         return fail(KVD_ERR_MISMATCH, "block sizes %u and %u: neither divides the other",
                     s.block_tokens, d.block_tokens);
     const uintptr_t sb = (uintptr_t)s.base, db = (uintptr_t)d.base;
-    if (sb < db + dst->extent_bytes && db < sb + src->extent_bytes)
+    if (sb < db + dst_extent && db < sb + src_extent)
         return fail(KVD_ERR_ALIAS, "source and destination pools overlap");
-
-    kvd_plan *p = new (std::nothrow) kvd_plan();
-    if (!p) return fail(KVD_ERR_INVALID, "out of host memory");
-    p->tag = kPlanTag;
     p->src = s;
     p->dst = d;
     p->max_requests = max_requests;
@@ -438,29 +440,21 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     const bool beyond32 = (uint64_t)s.num_blocks * s.stride_block * e >= (1ull << 36) ||
                           (uint64_t)d.num_blocks * d.stride_block * e >= (1ull << 36);
     g.wide = (p->fold_layers && (beyond32 || (flags & KVD_PLAN_WIDE_OFFSETS))) ? 1u : 0u;
-    if (!p->fold_layers && (block_axis_bytes(s) >= (1ull << 36) || block_axis_bytes(d) >= (1ull << 36))) {
-        delete p;
+    if (!p->fold_layers && (block_axis_bytes(s) >= (1ull << 36) || block_axis_bytes(d) >= (1ull << 36)))
         return fail(KVD_ERR_RANGE, "a block axis that spans more than 64 GiB needs block-major pools with the same inner "
                                    "order on both sides");
-    }
-    if ((flags & KVD_PLAN_WIDE_OFFSETS) && !p->fold_layers) {
-        delete p;
+    if ((flags & KVD_PLAN_WIDE_OFFSETS) && !p->fold_layers)
         return fail(KVD_ERR_MISMATCH, "48-bit offsets are for block-major pools with the same inner order on both sides");
-    }
-    if ((flags & KVD_PLAN_PERSISTENT) && g.wide) {
-        delete p;
+    if ((flags & KVD_PLAN_PERSISTENT) && g.wide)
         return fail(KVD_ERR_MISMATCH, "the persistent form has 32-bit offsets only");
-    }
     const uint32_t hk_max = p->fold_layers ? g.hk * std::min(s.num_layers, d.num_layers) : g.hk;
     g.rows_per_item = g.du <= kChunkUnits ? kChunkUnits / g.du : 0;
     p->by_descriptor = g.mode >= kRelayoutHT2TH && !(flags & (KVD_PLAN_PERSISTENT | KVD_PLAN_QUEUE_ORDER)) &&
                        s.stride_block > s.stride_layer && s.stride_block > s.stride_kv &&
                        d.stride_block > d.stride_layer && d.stride_block > d.stride_kv;
     p->items_per_desc = g.rows_per_item ? ceil_div(tmin * g.hk, g.rows_per_item) : 0;
-    if ((flags & KVD_PLAN_WHOLE_BLOCKS) && s.block_tokens != d.block_tokens) {
-        delete p;
+    if ((flags & KVD_PLAN_WHOLE_BLOCKS) && s.block_tokens != d.block_tokens)
         return fail(KVD_ERR_MISMATCH, "whole-block transfers need equal block sizes");
-    }
     g.div_du = make_fastdiv(g.du);
     g.div_hk = make_fastdiv(g.hk);
     g.div_tb_src = make_fastdiv(g.tb_src);
@@ -478,10 +472,7 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
         p->max_items = pieces_max * tmin * g.hk / g.rows_per_item + p->max_txns + 1;
     else
         p->max_items = units_max / kChunkUnits + p->max_txns + 1;
-    if (p->max_items >= (1ull << 31) || p->max_txns >= (1ull << 31)) {
-        delete p;
-        return fail(KVD_ERR_CAPACITY, "plan capacity too large");
-    }
+    if (p->max_items >= (1ull << 31) || p->max_txns >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "plan capacity too large");
     // destination regions for kvd_order_kernel: 2 MiB, or wider if the slab's block axis would
     // need more buckets than the kernel keeps
     const uint64_t dst_span16 = ((uint64_t)(d.num_blocks - 1) * d.stride_block +
@@ -489,7 +480,108 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     p->order_shift = 17;
     while ((dst_span16 >> p->order_shift) >= kOrderBuckets) ++p->order_shift;
     p->order_stale = true;
-    p->dst_used.assign(d.num_blocks, 0);
+    return KVD_OK;
+}
+
+// ------------------------------------------------------------------ the entry point that allocates nothing
+//
+// kvd_pull_noalloc serves callers that cannot allocate device memory.  What a plan keeps in
+// hipMalloc / hipHostMalloc memory - the block tables, descriptors, work items, their region-ordered
+// copy, the header - lives here in one array that is part of the code object, carved up at fixed
+// offsets.  Every GPU the library is used on holds its own copy at its own address until the
+// process ends; the name below is a host-side stand-in for it, so host code only ever uses the
+// address hipGetSymbolAddress returns for the current device.
+constexpr uint32_t kNaMaxBlocks = KVD_NOALLOC_MAX_BLOCKS;  // block-table entries per side
+constexpr uint32_t kNaMaxTxns = 1u << 17;                  // read transactions before merging
+constexpr uint32_t kNaMaxItems = KVD_NOALLOC_MAX_WORK_ITEMS;
+constexpr size_t kNaOffTablesSrc = 0;
+constexpr size_t kNaOffTablesDst = kNaOffTablesSrc + (size_t)kNaMaxBlocks * sizeof(int32_t);
+constexpr size_t kNaOffHeader = kNaOffTablesDst + (size_t)kNaMaxBlocks * sizeof(int32_t);  // header, then the build's "done" word
+constexpr size_t kNaOffDesc = kNaOffHeader + 256;
+constexpr size_t kNaOffDescHi = kNaOffDesc + (size_t)kNaMaxTxns * sizeof(Desc);
+constexpr size_t kNaOffItems = kNaOffDescHi + (size_t)kNaMaxTxns * sizeof(uint32_t);
+constexpr size_t kNaOffOrdered = kNaOffItems + (size_t)kNaMaxItems * sizeof(Item);
+constexpr size_t kNaScratchBytes = kNaOffOrdered + (size_t)kNaMaxItems * sizeof(Item);
+static_assert(kNaOffDesc % 256 == 0 && kNaOffDescHi % 256 == 0 && kNaOffItems % 256 == 0 && kNaOffOrdered % 256 == 0,
+              "every part of the scratch array starts on a 256-byte boundary");
+static_assert(sizeof(Header) + sizeof(uint32_t) <= 128, "header and done word share the 256 bytes at kNaOffHeader");
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kNaScratchBytes];
+
+namespace {
+
+constexpr int kNaMaxDevices = 64;
+
+// Per device: the address of that device's copy of the array.  Set up at the first call on the device.
+struct NoAllocDevice {
+    bool ready;
+    unsigned char *ptr;
+    int num_cus;
+};
+NoAllocDevice g_na[kNaMaxDevices];
+std::mutex g_na_setup;
+thread_local int32_t g_na_sorted[kNaMaxBlocks];  // host work space of the duplicate check
+
+int noalloc_device(NoAllocDevice **out)
+{
+    int dev = 0;
+    KVD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kNaMaxDevices) return fail(KVD_ERR_INVALID, "device %d: only devices below %d are supported", dev, kNaMaxDevices);
+    NoAllocDevice &nd = g_na[dev];
+    std::lock_guard<std::mutex> lock(g_na_setup);
+    if (!nd.ready) {
+        unsigned char *ptr = nullptr;
+        KVD_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr % 256)) return fail(KVD_ERR_HIP, "the scratch array has no usable address on device %d", dev);
+        hipDeviceProp_t prop;
+        KVD_HIP(hipGetDeviceProperties(&prop, dev));
+        nd.ptr = ptr;
+        nd.num_cus = prop.multiProcessorCount;
+        nd.ready = true;
+    }
+    *out = &nd;
+    return KVD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *kvd_last_error(void) { return g_err; }
+
+int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out)
+{
+    if (!desc || !out) return fail(KVD_ERR_INVALID, "null argument");
+    *out = nullptr;
+    uint64_t extent = 0;
+    int rc = check_pool_desc(*desc, &extent);
+    if (rc != KVD_OK) return rc;
+    kvd_pool *p = new (std::nothrow) kvd_pool;
+    if (!p) return fail(KVD_ERR_INVALID, "out of host memory");
+    p->tag = kPoolTag;
+    p->d = *desc;
+    p->extent_bytes = extent;
+    *out = p;
+    return KVD_OK;
+}
+
+int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_requests,
+                    uint32_t max_total_blocks, uint32_t flags, kvd_plan_t **out)
+{
+    if (!src || !dst || !out) return fail(KVD_ERR_INVALID, "null argument");
+    *out = nullptr;
+    if (src->tag != kPoolTag || dst->tag != kPoolTag) return fail(KVD_ERR_INVALID, "not a pool handle");
+    kvd_plan *p = new (std::nothrow) kvd_plan();
+    if (!p) return fail(KVD_ERR_INVALID, "out of host memory");
+    const int rc = init_plan(p, src->d, src->extent_bytes, dst->d, dst->extent_bytes, max_requests, max_total_blocks, flags);
+    if (rc != KVD_OK) {
+        delete p;
+        return rc;
+    }
+    p->tag = kPlanTag;
+    p->dst_used.assign(dst->d.num_blocks, 0);
     p->reqs.reserve(max_requests);
     p->allocated = false;
     *out = p;
@@ -635,26 +727,12 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
             batch_txn += n_txn;
             batch_items += items;
         }
-        BuildArgs a;
-        a.tables_src = p->tables_src_dev;
-        a.tables_dst = p->tables_dst_dev;
+        BuildArgs a = build_args(p, g, layer_begin, n_layers, batch_txn, batch_items);
         a.reqs = p->reqs_pinned_dev + b0;
         a.first = p->reqs_pinned[b0];
-        a.desc = p->desc_dev;
-        a.desc_hi = p->desc_hi_dev;
-        a.items = p->items_dev;
-        a.hdr = p->hdr_dev;
         a.n_req = nb;
-        a.base_src16 = p->fold_layers ? (uint32_t)(layer_begin * g.src_layer_bytes / kUnitBytes) : 0u;
-        a.base_dst16 = p->fold_layers ? (uint32_t)(layer_begin * g.dst_layer_bytes / kUnitBytes) : 0u;
-        a.n_txn = batch_txn;
-        a.layers = p->fold_layers ? (1u << 16) : (layer_begin | (n_layers << 16));
         a.fresh = (b0 == 0) ? 1u : 0u;
         a.may_merge_prev = (b0 > first_new || same_layers) ? 1u : 0u;
-        a.no_coalesce = (p->flags & KVD_PLAN_NO_COALESCE) ? 1u : 0u;
-        a.expand_inline = batch_items <= kInlineItems ? 1u : 0u;
-        a.done = p->done_dev;
-        a.seq = ++p->build_seq;
         p->build_stream = (hipStream_t)stream;
         hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
         hipError_t launch = hipGetLastError();
@@ -705,6 +783,109 @@ int kvd_pull_layers(kvd_plan_t *p, uint32_t layer_begin, uint32_t layer_end, voi
     if (p->flags & KVD_PLAN_PERSISTENT) return fail(KVD_ERR_MISMATCH, "the persistent form moves whole plans only");
     if (p->reqs.empty()) return KVD_OK;
     return launch_pull(p, stream, false, layer_begin, layer_end);
+}
+
+int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, const int32_t *src_tbl, uint32_t n_src,
+                     const int32_t *dst_tbl, uint32_t n_dst, uint32_t seq_len, uint32_t layer_begin,
+                     uint32_t layer_end, uint32_t flags, void *stream)
+{
+    if (!src || !dst) return fail(KVD_ERR_INVALID, "null argument");
+    if (flags & ~(uint32_t)(KVD_PLAN_NO_COALESCE | KVD_PLAN_WHOLE_BLOCKS | KVD_PLAN_QUEUE_ORDER))
+        return fail(KVD_ERR_INVALID, "flags 0x%x: only KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS and KVD_PLAN_QUEUE_ORDER apply here", flags);
+    uint64_t src_extent = 0, dst_extent = 0;
+    int rc = check_pool_desc(*src, &src_extent);
+    if (rc != KVD_OK) return rc;
+    rc = check_pool_desc(*dst, &dst_extent);
+    if (rc != KVD_OK) return rc;
+    // a plan for this one call; it lives on the stack and its scratch pointers will point into the array
+    kvd_plan plan{};
+    kvd_plan *const p = &plan;
+    rc = init_plan(p, *src, src_extent, *dst, dst_extent, 1, kNaMaxBlocks, flags);
+    if (rc != KVD_OK) return rc;
+    p->max_txns = kNaMaxTxns;  // what the array holds, not what the block count could need
+    p->max_items = kNaMaxItems;
+    if (layer_begin >= layer_end) return fail(KVD_ERR_INVALID, "empty layer range [%u, %u)", layer_begin, layer_end);
+    if (layer_end > src->num_layers || layer_end > dst->num_layers)
+        return fail(KVD_ERR_RANGE, "layer range [%u, %u) outside a pool", layer_begin, layer_end);
+    if (seq_len > (1u << 30)) return fail(KVD_ERR_RANGE, "seq_len %u above 2^30", seq_len);
+    if (seq_len == 0) return KVD_OK;
+    if (!src_tbl || !dst_tbl) return fail(KVD_ERR_INVALID, "null block table");
+
+    const uint32_t n_layers = layer_end - layer_begin;
+    Geo g = p->geo;
+    if (p->fold_layers) {  // block-major pools: this call's layers become planes of the block
+        g.hk = p->planes_per_layer * n_layers;
+        g.div_hk = make_fastdiv(g.hk);
+    }
+    const uint32_t slab_layers = p->fold_layers ? 1u : n_layers;
+    const uint32_t len = (flags & KVD_PLAN_WHOLE_BLOCKS) ? ceil_div(seq_len, g.tb_src) * g.tb_src : seq_len;
+    const uint32_t need_src = ceil_div(len, g.tb_src), need_dst = ceil_div(len, g.tb_dst);
+    if (need_src > kNaMaxBlocks || need_dst > kNaMaxBlocks)
+        return fail(KVD_ERR_CAPACITY, "%u tokens need %u source and %u destination blocks; this entry point takes at most %u per side",
+                    len, need_src, need_dst, kNaMaxBlocks);
+    if (n_src < need_src || n_dst < need_dst)
+        return fail(KVD_ERR_RANGE, "block table too short for %u tokens (source %u of %u, destination %u of %u)", len, n_src,
+                    need_src, n_dst, need_dst);
+    uint32_t n_txn = 0, items = 0;
+    request_sizes(g, len, &n_txn, &items);
+    if (n_txn > kNaMaxTxns || items > kNaMaxItems)
+        return fail(KVD_ERR_CAPACITY, "the request needs %u read transactions and %u work items; this entry point takes at most %u and %u",
+                    n_txn, items, kNaMaxTxns, kNaMaxItems);
+    for (uint32_t i = 0; i < need_src; ++i)
+        if (src_tbl[i] < 0 || (uint32_t)src_tbl[i] >= src->num_blocks)
+            return fail(KVD_ERR_RANGE, "source block id %d at entry %u outside [0, %u)", src_tbl[i], i, src->num_blocks);
+    for (uint32_t i = 0; i < need_dst; ++i)
+        if (dst_tbl[i] < 0 || (uint32_t)dst_tbl[i] >= dst->num_blocks)
+            return fail(KVD_ERR_RANGE, "destination block id %d at entry %u outside [0, %u)", dst_tbl[i], i, dst->num_blocks);
+    // every destination byte is written at most once: no destination block twice
+    std::copy(dst_tbl, dst_tbl + need_dst, g_na_sorted);
+    std::sort(g_na_sorted, g_na_sorted + need_dst);
+    for (uint32_t i = 1; i < need_dst; ++i)
+        if (g_na_sorted[i] == g_na_sorted[i - 1])
+            return fail(KVD_ERR_ALIAS, "destination block %d appears twice in the table", g_na_sorted[i]);
+
+    NoAllocDevice *nd = nullptr;
+    rc = noalloc_device(&nd);
+    if (rc != KVD_OK) return rc;
+    unsigned char *const ptr = nd->ptr;  // this device's copy of the array
+    p->num_cus = nd->num_cus;
+    p->tables_src_dev = (int32_t *)(ptr + kNaOffTablesSrc);
+    p->tables_dst_dev = (int32_t *)(ptr + kNaOffTablesDst);
+    p->hdr_dev = (Header *)(ptr + kNaOffHeader);
+    p->done_dev = (uint32_t *)(ptr + kNaOffHeader + 128);  // nobody waits for it: the tables were passed by value
+    p->desc_dev = (Desc *)(ptr + kNaOffDesc);
+    p->desc_hi_dev = (uint32_t *)(ptr + kNaOffDescHi);
+    p->items_dev = (Item *)(ptr + kNaOffItems);
+    p->ordered_dev = (Item *)(ptr + kNaOffOrdered);
+    // the host's bookkeeping of a plan that holds this one request
+    p->txns_total = n_txn;
+    p->item_bound = items;
+    p->payload_bytes = ((uint64_t)len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
+    p->max_layers = slab_layers;
+    p->order_stale = true;
+
+    // the tables, a piece at a time through the kernel's arguments, into the array
+    hipStream_t st = (hipStream_t)stream;
+    for (uint32_t off = 0; off < std::max(need_src, need_dst); off += kArgTableEntries) {
+        TableChunk c{};
+        const uint32_t ns = off < need_src ? std::min(kArgTableEntries, need_src - off) : 0u;
+        const uint32_t nt = off < need_dst ? std::min(kArgTableEntries, need_dst - off) : 0u;
+        if (ns) memcpy(c.src, src_tbl + off, (size_t)ns * sizeof(int32_t));
+        if (nt) memcpy(c.dst, dst_tbl + off, (size_t)nt * sizeof(int32_t));
+        hipLaunchKernelGGL(kvd_stage_tables_kernel, dim3(1), dim3(kArgTableEntries), 0, st, c, p->tables_src_dev + off, ns,
+                           p->tables_dst_dev + off, nt);
+        KVD_HIP(hipGetLastError());
+    }
+    BuildArgs a = build_args(p, g, layer_begin, n_layers, n_txn, items);
+    a.first = ReqDev{0, 0, len, 0};
+    hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, st, g, a);
+    KVD_HIP(hipGetLastError());
+    if (!a.expand_inline) {
+        hipLaunchKernelGGL(kvd_expand_kernel, dim3(items / 256 + 1), dim3(256), 0, st, g, p->desc_dev, p->desc_hi_dev,
+                           p->items_dev, p->hdr_dev, a.layers);
+        KVD_HIP(hipGetLastError());
+    }
+    return launch_pull(p, stream, true, 0, 0);
 }
 
 int kvd_complete(uint64_t *flag, uint64_t value, void *stream)

@@ -443,6 +443,24 @@ __global__ __launch_bounds__(256) void kvd_expand_kernel(Geo g, const Desc *desc
     items[c] = make_item(g, d, g.wide ? desc_hi[lo] : 0u, c - d.prefix, layers);
 }
 
+// A piece of the host's two block tables carried in the kernel's argument buffer and written to
+// device memory: the way the tables reach the GPU for a caller that has no pinned memory to put
+// them in.  2 * 448 ids fill 3584 of the 4096 bytes a kernel's arguments may take.
+constexpr uint32_t kArgTableEntries = 448;
+
+struct TableChunk {
+    int32_t src[kArgTableEntries];
+    int32_t dst[kArgTableEntries];
+};
+
+__global__ __launch_bounds__(kArgTableEntries) void kvd_stage_tables_kernel(TableChunk c, int32_t *tables_src, uint32_t n_src,
+                                                                            int32_t *tables_dst, uint32_t n_dst)
+{
+    const uint32_t i = threadIdx.x;
+    if (i < n_src) tables_src[i] = c.src[i];
+    if (i < n_dst) tables_dst[i] = c.dst[i];
+}
+
 // ------------------------------------------------------------------ pull
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

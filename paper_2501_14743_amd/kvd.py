@@ -20,6 +20,8 @@ KVD_OK = 0
 KVD_ERR_INVALID, KVD_ERR_RANGE, KVD_ERR_MISMATCH = -1, -2, -3
 KVD_ERR_ALIAS, KVD_ERR_CAPACITY, KVD_ERR_HIP = -4, -5, -6
 KVD_LAYOUT_BHTD, KVD_LAYOUT_BTHD = 0, 1
+KVD_NOALLOC_MAX_BLOCKS = 8192
+KVD_NOALLOC_MAX_WORK_ITEMS = 1 << 19
 KVD_PLAN_NO_COALESCE = 1
 KVD_PLAN_PERSISTENT = 2
 KVD_PLAN_WHOLE_BLOCKS = 4
@@ -87,6 +89,8 @@ def lib() -> ctypes.CDLL:
                                               u32, u32, vp]
     L.kvd_pull.argtypes = [vp, vp]
     L.kvd_pull_layers.argtypes = [vp, u32, u32, vp]
+    L.kvd_pull_noalloc.argtypes = [ctypes.POINTER(kvd_pool_desc_t), ctypes.POINTER(kvd_pool_desc_t), i32p, u32, i32p, u32,
+                                   u32, u32, u32, u32, vp]
     L.kvd_complete.argtypes = [vp, u64, vp]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
     L.kvd_pull_staged.argtypes = [vp, vp, vp, u64, vp]
@@ -98,7 +102,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
-                 "kvd_pull_layers", "kvd_complete",
+                 "kvd_pull_layers", "kvd_pull_noalloc", "kvd_complete",
                  "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain"):
         getattr(L, name).restype = ctypes.c_int
@@ -168,6 +172,22 @@ def kvd_pull(plan: int, stream: int = 0) -> None:
 
 def kvd_pull_layers(plan: int, layer_begin: int, layer_end: int, stream: int = 0) -> None:
     _check(lib().kvd_pull_layers(plan, layer_begin, layer_end, stream))
+
+
+def pool_desc(base: int, geometry, stride_layer=None, stride_kv=None, stride_block=None) -> kvd_pool_desc_t:
+    """kvd_pool_desc_t of a pool at `base` with the given geometry (strides from the geometry unless given)."""
+    g = geometry
+    return kvd_pool_desc_t(base, g.num_layers, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes,
+                           LAYOUTS.get(g.layout, g.layout), g.stride_layer if stride_layer is None else stride_layer,
+                           g.stride_kv if stride_kv is None else stride_kv,
+                           g.stride_block if stride_block is None else stride_block)
+
+
+def kvd_pull_noalloc(src_desc: kvd_pool_desc_t, dst_desc: kvd_pool_desc_t, src_block_table, dst_block_table,
+                     seq_len: int, layer_begin: int, layer_end: int, flags: int = 0, stream: int = 0) -> None:
+    st, dt = _table(src_block_table), _table(dst_block_table)
+    _check(lib().kvd_pull_noalloc(ctypes.byref(src_desc), ctypes.byref(dst_desc), _i32p(st), st.size, _i32p(dt), dt.size,
+                                  seq_len, layer_begin, layer_end, flags, stream))
 
 
 def kvd_complete(flag_ptr: int, value: int, stream: int = 0) -> None:
