@@ -17,9 +17,16 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def _checker():
+    """The CPU oracle's test glue (tests/): loaded only by the cpu_baseline leg and by the check of
+    the result after the timed steps, never by the timed path."""
+    tests = os.path.join(ROOT, "tests")
+    if tests not in sys.path:
+        sys.path.insert(0, tests)
 
 PEAK_HBM_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 METRIC = "achieved HBM GB/s (% of peak) for paged KV pull; µs per 8K-token request"
@@ -29,22 +36,58 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def cpu_baseline(cfg_no: int, budget_s: float = 12.0) -> dict:
-    """Time the oracle (as it stands, one thread) on a bounded sample: layer 0 of the same
-    workload, repeated (at most 256 times) until about `budget_s` seconds of CPU work have been spent."""
-    import numpy as np
-    import kvd_testlib as tl
+def _one_layer_workload(cfg_no: int):
     from paper_2501_14743_amd import workloads as wl
-
     full = wl.CONFIGS[cfg_no]()
-    gs = wl.PoolGeometry(1, full.src.num_blocks, full.src.block_tokens, full.src.num_kv_heads,
-                         full.src.head_dim, full.src.elem_bytes, full.src.layout)
-    gd = wl.PoolGeometry(1, full.dst.num_blocks, full.dst.block_tokens, full.dst.num_kv_heads,
-                         full.dst.head_dim, full.dst.elem_bytes, full.dst.layout)
+    gs, gd = (wl.PoolGeometry(1, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes, g.layout)
+              for g in (full.src, full.dst))
     w = wl.Workload(full.name, gs, gd, full.requests, full.dtype, full.seed)
-    src = np.ones(gs.total_bytes, np.uint8)
-    dst = np.ones(gd.total_bytes, np.uint8)
     payload = w.total_tokens * 2 * gs.num_kv_heads * gs.head_dim * gs.elem_bytes
+    return full, w, payload
+
+
+def _oracle_worker(cfg_no: int, reps: int, barrier, out) -> None:
+    """One host core's share of the all-core leg: the oracle on one layer (K and V) of the workload,
+    on pools of this process's own."""
+    import numpy as np
+    _checker()
+    import kvd_testlib as tl
+    _, w, _ = _one_layer_workload(cfg_no)
+    src = np.ones(w.src.total_bytes, np.uint8)
+    dst = np.empty(w.dst.total_bytes, np.uint8)
+    tl.oracle_pull_workload(w, src, dst)  # untimed: pages in what the pull touches
+    barrier.wait()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        tl.oracle_pull_workload(w, src, dst)
+    out.put(time.perf_counter() - t0)
+
+
+def host_cores() -> int:
+    """Cores this process may use: its affinity mask, capped by the thread count the environment
+    sets for the machine's CPU share (OMP_NUM_THREADS), at most 16."""
+    n = len(os.sched_getaffinity(0))
+    try:
+        n = min(n, int(os.environ.get("OMP_NUM_THREADS", n)))
+    except ValueError:
+        pass
+    return max(1, min(n, 16))
+
+
+def cpu_baseline(cfg_no: int, budget_s: float = 10.0) -> dict:
+    """Time the oracle as it stands on a bounded sample of the workload: one layer (K and V), repeated
+    until about `budget_s` seconds of work have been spent, first on one core, then on all host cores
+    at once (one worker process per core, each moving one layer on pools of its own: the layers of a
+    request share its block tables, so every worker does what one layer of the workload costs).
+    Must run before this process touches the GPU: the workers are forked."""
+    import multiprocessing as mp
+    import numpy as np
+    _checker()
+    import kvd_testlib as tl
+
+    full, w, payload = _one_layer_workload(cfg_no)
+    src = np.ones(w.src.total_bytes, np.uint8)
+    dst = np.empty(w.dst.total_bytes, np.uint8)
     t0 = time.perf_counter()
     tl.oracle_pull_workload(w, src, dst)
     first = time.perf_counter() - t0
@@ -53,11 +96,26 @@ def cpu_baseline(cfg_no: int, budget_s: float = 12.0) -> dict:
     for _ in range(reps):
         tl.oracle_pull_workload(w, src, dst)
     dt = (time.perf_counter() - t0) / reps
+    del src, dst
+    one = 2 * payload / dt / 1e9
+
+    cores = host_cores()
+    ctx = mp.get_context("fork")
+    barrier, out = ctx.Barrier(cores), ctx.Queue()
+    procs = [ctx.Process(target=_oracle_worker, args=(cfg_no, reps, barrier, out)) for _ in range(cores)]
+    for p in procs:
+        p.start()
+    times = [out.get(timeout=600) for _ in procs]
+    for p in procs:
+        p.join()
+    all_cores = cores * reps * 2 * payload / max(times) / 1e9
     return {
-        "value": 2 * payload / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": f"layer 0 (K and V) of {full.name}: {w.total_tokens} tokens, {payload} payload bytes, "
-                  f"mean of {reps} passes after one untimed pass; host has {os.cpu_count()} cpus",
-        "seconds_per_layer": dt,
+        "value": all_cores, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": f"one layer (K and V) of {full.name} per core: {w.total_tokens} tokens, {payload} payload bytes, "
+                  f"{reps} passes per worker process after one untimed pass, {cores} worker processes at once "
+                  f"(slowest worker's time); host shows {os.cpu_count()} cpus, affinity {len(os.sched_getaffinity(0))}",
+        "one_core": {"value": one, "unit": "GB/s", "cores": 1, "seconds_per_layer": dt},
+        "seconds_per_layer_all_cores_busy": max(times) / reps,
     }
 
 
@@ -90,10 +148,18 @@ def main() -> int:
               "run with --gpus 1", file=sys.stderr)
         return 2
 
+    # the CPU leg runs first: its worker processes are forked, which must happen before this
+    # process touches the GPU, and it must not share the host with the timed GPU steps
+    cpu = None
+    if not args.no_cpu_baseline:
+        log("timing the oracle on the host (one core, then all cores)")
+        cpu = cpu_baseline(args.config)
+        log(f"oracle: {cpu['one_core']['value']:.2f} GB/s on one core, {cpu['value']:.2f} GB/s on {cpu['cores']} cores")
+
     import numpy as np
     import torch
     from paper_2501_14743_amd import kvd, workloads as wl
-    import kvd_gpu as G
+    from paper_2501_14743_amd import device as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     kvd.lib()  # fail now if the library is missing
@@ -125,11 +191,16 @@ def main() -> int:
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(0, args.steps, stride)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    returned = np.empty(args.steps + 1)  # when each step's calls returned to the host
+    t0 = returned[0] = time.perf_counter()
     for i in range(args.steps):
         step(events[i // stride] if i % stride == 0 else None)
+        returned[i + 1] = time.perf_counter()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # host time per step: in the steady state the host waits in kvd_plan_reset for the previous
+    # step's build, so this follows the GPU's step time; an outlier is a call that blocked
+    host_us = np.diff(returned) * 1e6
     stats = x.plan.stats(sh)  # of the last step's plan
     payload = stats["payload_bytes"]
     pull_ms = np.array([a.elapsed_time(b) for a, b in events])
@@ -139,10 +210,13 @@ def main() -> int:
     log(f"step {ms_per_step * 1e3:.1f} us, pull kernel mean {pull_ms.mean() * 1e3:.1f} us "
         f"(min {pull_ms.min() * 1e3:.1f}), {achieved:.0f} GB/s = {achieved / PEAK_HBM_GBPS:.1%} of peak")
 
-    # the timed work produced the right bytes: oracle on one layer
-    check_layer = w.layer_end - 1
-    G.compare_layer_with_oracle(w, src, dst, check_layer)
-    log(f"layer {check_layer} matches the oracle")
+    # the timed work produced the right bytes: oracle on the first and the last layer
+    _checker()
+    import kvd_gpu
+    check_layers = sorted({w.layer_begin, w.layer_end - 1})
+    for layer in check_layers:
+        kvd_gpu.compare_layer_with_oracle(w, src, dst, layer)
+    log(f"layers {check_layers} match the oracle")
 
     extras = {}
     if not args.no_extras:
@@ -391,6 +465,9 @@ def main() -> int:
     from paper_2501_14743_amd import traffic as traffic_record
     rec = traffic_record.load_record(w.name)
     traffic = rec["traffic_bytes_per_launch"] if rec else None
+    # the counters cannot be read inside this run: the figure comes from the recorded rocprofv3 --pmc
+    # runs of this same kernel source on this workload (profiles/), or is null when there is none
+    traffic_source = "recorded rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this kernel source" if rec else None
 
     out = {
         "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -406,16 +483,17 @@ def main() -> int:
         "us_per_request_batch": ms_per_step * 1e3,
         "pct_of_peak": 100.0 * achieved / PEAK_HBM_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                     "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic,
+                     "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "kvd_pull_kernel", "kernel_us_mean": float(pull_ms.mean() * 1e3),
                      "kernel_us_min": float(pull_ms.min() * 1e3), "launches_timed": int(pull_ms.size),
                      "algorithmic_bytes_per_launch": 2 * payload},
-        "verified": f"layer {check_layer} bit-exact vs oracle after the timed steps",
+        "step_host_us": {"p50": float(np.percentile(host_us, 50)), "p99": float(np.percentile(host_us, 99)),
+                         "max": float(host_us.max()), "max_at_step": int(host_us.argmax())},
+        "verified": f"layers {check_layers} bit-exact vs oracle after the timed steps",
         "extras": extras,
     }
-    if not args.no_cpu_baseline:
-        log("timing the oracle on the host")
-        out["cpu_baseline"] = cpu_baseline(args.config)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
     x.close()
     return 0

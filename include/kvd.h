@@ -182,7 +182,9 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
  * moved, K and V.  seq_len == 0 appends nothing and succeeds.
  *
  * Address translation and coalescing run in a kernel enqueued on `stream`; kvd_pull must be
- * enqueued on the same stream (or be ordered after it by the caller).  `stream` must not be
+ * enqueued on the same stream (or be ordered after it by the caller).  Builds of one plan normally
+ * use one stream; a build on another stream than the plan's previous one first waits on the host
+ * until that one has read its tables (the caller still orders the two streams' kernels).  `stream` must not be
  * recording a HIP graph (KVD_ERR_INVALID): the host part of the call happens at once.
  *
  * Errors (checked on the host before anything is enqueued; the plan is unchanged on error):
@@ -327,7 +329,10 @@ int kvd_plan_get_descriptors(kvd_plan_t *plan, void *stream, kvd_span_t *spans,
  */
 int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream);
 
-/* Release a pool or a plan (NULL is allowed).  Frees the plan's own scratch, never pool memory. */
+/* Release a pool or a plan (NULL is allowed).  Frees the plan's own scratch, never pool memory.
+ * The library keeps a list of the handles it has given out: a pointer that is not on it (released
+ * before, or never a handle) is ignored here without being read, and refused with KVD_ERR_INVALID
+ * by every other call. */
 void kvd_free(void *handle);
 
 /* Message for the last error on this thread ("" if none). */

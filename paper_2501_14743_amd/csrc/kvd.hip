@@ -13,6 +13,7 @@
 #include <mutex>
 #include <new>
 #include <thread>
+#include <unordered_set>
 #include <vector>
 
 #include "kvd.h"
@@ -40,6 +41,31 @@ int fail(int code, const char *fmt, ...)
 
 constexpr uint32_t kPoolTag = 0x6b76504fu;  // handle type tags
 constexpr uint32_t kPlanTag = 0x6b76504cu;
+
+// Every handle this library has given out and not yet released.  A pointer is looked up here
+// before it is dereferenced, so a stale, foreign or already released handle is refused instead of
+// being read.  Guarded by a mutex; a lookup costs some tens of nanoseconds per call.
+std::mutex g_handles_mutex;
+std::unordered_set<const void *> g_handles;
+
+void register_handle(const void *h)
+{
+    std::lock_guard<std::mutex> lock(g_handles_mutex);
+    g_handles.insert(h);
+}
+
+bool is_live_handle(const void *h)
+{
+    std::lock_guard<std::mutex> lock(g_handles_mutex);
+    return g_handles.count(h) != 0;
+}
+
+// True if h was live; it no longer is afterwards.
+bool retire_handle(const void *h)
+{
+    std::lock_guard<std::mutex> lock(g_handles_mutex);
+    return g_handles.erase(h) != 0;
+}
 
 struct ReqHost {
     uint32_t table_off_src, table_off_dst;  // into the plan's table mirrors
@@ -283,8 +309,16 @@ bool is_capturing(void *stream)
 
 kvd_plan *as_plan(void *h)
 {
+    if (!h || !is_live_handle(h)) return nullptr;
     kvd_plan *p = (kvd_plan *)h;
-    return (p && p->tag == kPlanTag) ? p : nullptr;
+    return p->tag == kPlanTag ? p : nullptr;
+}
+
+const kvd_pool *as_pool(const void *h)
+{
+    if (!h || !is_live_handle(h)) return nullptr;
+    const kvd_pool *p = (const kvd_pool *)h;
+    return p->tag == kPoolTag ? p : nullptr;
 }
 
 // The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
@@ -563,6 +597,7 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out)
     p->tag = kPoolTag;
     p->d = *desc;
     p->extent_bytes = extent;
+    register_handle(p);
     *out = p;
     return KVD_OK;
 }
@@ -572,7 +607,7 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
 {
     if (!src || !dst || !out) return fail(KVD_ERR_INVALID, "null argument");
     *out = nullptr;
-    if (src->tag != kPoolTag || dst->tag != kPoolTag) return fail(KVD_ERR_INVALID, "not a pool handle");
+    if (!as_pool(src) || !as_pool(dst)) return fail(KVD_ERR_INVALID, "not a pool handle");
     kvd_plan *p = new (std::nothrow) kvd_plan();
     if (!p) return fail(KVD_ERR_INVALID, "out of host memory");
     const int rc = init_plan(p, src->d, src->extent_bytes, dst->d, dst->extent_bytes, max_requests, max_total_blocks, flags);
@@ -584,6 +619,7 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
     p->dst_used.assign(dst->d.num_blocks, 0);
     p->reqs.reserve(max_requests);
     p->allocated = false;
+    register_handle(p);
     *out = p;
     return KVD_OK;
 }
@@ -687,6 +723,10 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         }
     }
     int rc = ensure_allocated(p);
+    // Build kernels report through one word, in launch order.  Kernels on two streams could finish
+    // in the other order and leave the older number in it, so a build on another stream than the
+    // last one first waits until that one has reported.
+    if (rc == KVD_OK && p->build_seq > 0 && (hipStream_t)stream != p->build_stream) rc = wait_for_builds(p);
     if (rc != KVD_OK) {
         unmark_call(n_requests, 0);
         return rc;
@@ -1055,7 +1095,9 @@ int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream)
 
 void kvd_free(void *handle)
 {
-    if (!handle) return;
+    // only a handle that is still on the list of live ones is touched: a second release of the
+    // same handle, or a pointer that never was one, is ignored without being read
+    if (!handle || !retire_handle(handle)) return;
     const uint32_t tag = *(const uint32_t *)handle;
     if (tag == kPoolTag) {
         kvd_pool *p = (kvd_pool *)handle;

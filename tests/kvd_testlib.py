@@ -66,39 +66,33 @@ def oracle_plan_descriptors_block_major(w: wl.Workload) -> np.ndarray:
     block: for every piece of a request (tokens that share one block on both sides), the
     transactions of layer_begin, layer_begin+1, ... in turn.  In pools that keep all layers of a
     block together that is the order in which consecutive ranges continue each other, so section
-    4.2 merges a block's layers.  Offsets are relative to the pool."""
-    tmin = min(w.src.block_tokens, w.dst.block_tokens)
+    4.2 merges a block's layers.  Offsets are relative to the pool.
+
+    A piece's transactions in one layer's tensor are what the oracle's list for that tensor gains
+    when the request is cut one piece later: the list of the shorter request is a prefix of the
+    longer one's (asserted).  To keep this linear, the cuts are taken inside one block of the side
+    with the larger blocks at a time, on tables that start at that block."""
+    ls, ld = w.src.block_tokens, w.dst.block_tokens
+    tmin, tmax = min(ls, ld), max(ls, ld)
     s_all, d_all = oracle_tensors(w.src, None), oracle_tensors(w.dst, None)
+    layers = range(w.layer_begin, w.layer_end)
     queue = []
     for r in w.requests:
-        per_layer = {}
-        for layer in range(w.layer_begin, w.layer_end):
-            t = orc.request_transactions(s_all[layer], d_all[layer], -1, r.src_table, r.dst_table, r.seq_len)
-            t[:, 0] += layer * w.src.stride_layer * w.src.elem_bytes
-            t[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
-            per_layer[layer] = t
-        # where each piece's transactions end inside a layer's list: the list of the request cut
-        # after a piece is a prefix of the full list (pieces are enumerated independently), and
-        # every whole piece contributes as many transactions as the first one; a few cuts are
-        # taken from the oracle itself to make sure of that
-        first, total = w.layer_begin, len(per_layer[w.layer_begin])
-
-        def count_upto(t1):
-            return len(orc.request_transactions(s_all[first], d_all[first], -1, r.src_table, r.dst_table, min(t1, r.seq_len)))
-        n_whole = r.seq_len // tmin
-        per_piece = count_upto(tmin) if n_whole else 0
-        ends = [per_piece * (k + 1) for k in range(n_whole)]
-        if r.seq_len % tmin:
-            ends.append(total)
-        assert ends[-1] == total
-        for k in sorted({0, n_whole // 3, n_whole // 2, n_whole - 1} & set(range(n_whole))):
-            assert count_upto((k + 1) * tmin) == ends[k]
-        lo = 0
-        for hi in ends:
-            for layer in range(w.layer_begin, w.layer_end):
-                assert len(per_layer[layer]) == ends[-1]
-                queue.append(per_layer[layer][lo:hi])
-            lo = hi
+        for big in range(0, r.seq_len, tmax):
+            st, dt = r.src_table[big // ls:], r.dst_table[big // ld:]
+            have = {layer: np.zeros((0, 3), np.int64) for layer in layers}
+            for end in range(tmin, tmax + tmin, tmin):
+                end = min(end, r.seq_len - big)
+                for layer in layers:
+                    t = orc.request_transactions(s_all[layer], d_all[layer], -1, st, dt, end)
+                    t[:, 0] += layer * w.src.stride_layer * w.src.elem_bytes
+                    t[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
+                    n = len(have[layer])
+                    assert np.array_equal(t[:n], have[layer]) and len(t) > n
+                    queue.append(t[n:])
+                    have[layer] = t
+                if end == r.seq_len - big:
+                    break
     q = np.concatenate(queue) if queue else np.zeros((0, 3), np.int64)
     return orc.coalesce(q)
 

@@ -103,6 +103,28 @@ def test_plan_create_rejects_mismatch_and_overlap():
         kvd.kvd_plan_create(s.handle, 0, 1, 8)
 
 
+def test_released_and_foreign_handles_are_refused_without_being_read():
+    g = geom()
+    s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
+    plan = kvd.kvd_plan_create(s.handle, d.handle, 1, 8)
+    kvd.kvd_free(plan)
+    kvd.kvd_free(plan)                                    # second release: ignored
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull, plan)       # a released plan is no plan
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_plan_reset, plan)
+    old_pool = s.handle
+    s.close()
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_plan_create, old_pool, d.handle, 1, 8)
+    kvd.kvd_free(old_pool)
+    # memory that never was a handle, whatever it holds, and an address that is not mapped at all
+    fake = (ctypes.c_uint32 * 64)(*([0x6b76504c] * 64))   # looks like a plan's tag
+    kvd.kvd_free(ctypes.addressof(fake))
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull, ctypes.addressof(fake))
+    kvd.kvd_free(0x10)
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull, 0x10)
+    # a pool handle where a plan is expected
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull, d.handle)
+
+
 def test_build_descriptors_validates_before_launching():
     g = geom()
     s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
