@@ -11,6 +11,7 @@ timed region starts.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -129,6 +130,9 @@ def main() -> int:
                     help="HIP events bracket the pull kernel of every n-th timed step (an event record sits on the "
                          "GPU's queue between the build and the pull and costs that step a few microseconds)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gc-freeze", action="store_true",
+                    help="leave the objects alive before the timed region in the garbage collector's sight (shows the "
+                         "pause of a full collection as the longest step)")
     ap.add_argument("--no-extras", action="store_true", help="skip the reported GPU baselines")
     ap.add_argument("--no-slow-baselines", action="store_true",
                     help="skip the staged and the per-block memcpy baselines (hundreds of thousands of launches)")
@@ -175,18 +179,42 @@ def main() -> int:
 
     batch = len(w.requests) > 1  # several requests are appended with the one batched call
 
-    def step(ev=None):
+    calls = np.zeros((max(args.steps, 1), 3))  # host time inside reset / build / pull of every timed step
+    clock = time.perf_counter
+
+    def step(ev=None, i=None):
+        t0 = clock()
         x.plan.reset()
+        t1 = clock()
         x.build(batch)
+        t2 = clock()
         if ev is not None:
             ev[0].record(stream)
         x.plan.pull(sh)
         if ev is not None:
             ev[1].record(stream)
+        if i is not None:
+            calls[i] = (t1 - t0, t2 - t1, clock() - t2)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # CPython's cyclic garbage collector belongs to this harness, not to the library: a full
+    # collection over the million objects that torch and numpy keep alive takes tens of milliseconds
+    # and would land on whichever step's allocations trigger it.  Everything alive now is moved out
+    # of the collector's sight; collections that still happen inside the timed region are timed by
+    # a callback and reported.
+    if not args.no_gc_freeze:
+        gc.collect()
+        gc.freeze()
+    gc_pauses = []
+
+    def on_gc(phase, info, _start=[0.0]):
+        if phase == "start":
+            _start[0] = time.perf_counter()
+        else:
+            gc_pauses.append((info["generation"], (time.perf_counter() - _start[0]) * 1e3))
+    gc.callbacks.append(on_gc)
     stride = max(1, args.event_stride)
     events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
               for _ in range(0, args.steps, stride)]
@@ -194,10 +222,11 @@ def main() -> int:
     returned = np.empty(args.steps + 1)  # when each step's calls returned to the host
     t0 = returned[0] = time.perf_counter()
     for i in range(args.steps):
-        step(events[i // stride] if i % stride == 0 else None)
+        step(events[i // stride] if i % stride == 0 else None, i)
         returned[i + 1] = time.perf_counter()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    gc.callbacks.remove(on_gc)
     # host time per step: in the steady state the host waits in kvd_plan_reset for the previous
     # step's build, so this follows the GPU's step time; an outlier is a call that blocked
     host_us = np.diff(returned) * 1e6
@@ -329,24 +358,48 @@ def main() -> int:
             torch.cuda.synchronize()
             extras["per_layer_pulls_graph_replay_us"] = (time.perf_counter() - t) / 5 * 1e6
             del graph
+            # push mode next to the prefill's own compute: one 8192^3 bf16 GEMM stands in for a layer's
+            # prefill work on torch's stream; when it is done, that layer's KV is pulled on the transfer stream
+            # while the next layer's GEMM runs
             ma = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
             mb = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda")
+            mc = torch.empty(8192, 8192, dtype=torch.bfloat16, device="cuda")
+            compute = torch.cuda.Stream()  # same (default) priority as the transfer stream
+            compute.wait_stream(torch.cuda.current_stream())
+            done = [torch.cuda.Event() for _ in layers]
 
-            def gemms(n):
-                for _ in range(n):
-                    torch.matmul(ma, mb)
-            gemms(2)
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            gemms(10)
-            torch.cuda.synchronize()
-            extras["ten_gemms_alone_us"] = (time.perf_counter() - t) * 1e6
-            t = time.perf_counter()
-            gemms(10)
-            per_layer()
-            torch.cuda.synchronize()
-            extras["ten_gemms_with_per_layer_pulls_us"] = (time.perf_counter() - t) * 1e6
-            del ma, mb
+            def wall_us(fn):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t) * 1e6
+
+            def gemms_alone():
+                with torch.cuda.stream(compute):
+                    for _ in layers:
+                        torch.matmul(ma, mb, out=mc)
+
+            def gemms_with_pulls():
+                with torch.cuda.stream(compute):
+                    for k, layer in enumerate(layers):
+                        torch.matmul(ma, mb, out=mc)
+                        done[k].record(compute)
+                        stream.wait_event(done[k])
+                        x.plan.pull_layers(layer, layer + 1, sh)
+
+            def gemms_then_single_shot():
+                gemms_alone()
+                done[0].record(compute)
+                stream.wait_event(done[0])
+                x.plan.pull(sh)
+            for fn in (gemms_alone, gemms_with_pulls, gemms_then_single_shot):
+                fn()
+            extras["layer_gemms_alone_us"] = min(wall_us(gemms_alone) for _ in range(3))
+            extras["per_layer_pulls_alone_us"] = min(wall_us(per_layer_pulls) for _ in range(3))
+            extras["layer_gemms_with_per_layer_pulls_us"] = min(wall_us(gemms_with_pulls) for _ in range(3))
+            extras["layer_gemms_then_single_shot_pull_us"] = min(wall_us(gemms_then_single_shot) for _ in range(3))
+            del ma, mb, mc
             x.plan.reset()
             x.build(batch)
         # worst-case fragmentation (every block alone on both sides) of the same token count, in these pools and
@@ -488,7 +541,11 @@ def main() -> int:
                      "kernel_us_min": float(pull_ms.min() * 1e3), "launches_timed": int(pull_ms.size),
                      "algorithmic_bytes_per_launch": 2 * payload},
         "step_host_us": {"p50": float(np.percentile(host_us, 50)), "p99": float(np.percentile(host_us, 99)),
-                         "max": float(host_us.max()), "max_at_step": int(host_us.argmax())},
+                         "max": float(host_us.max()), "max_at_step": int(host_us.argmax()),
+                         "max_step_reset_build_pull_us": [float(v * 1e6) for v in calls[int(host_us.argmax())]],
+                         "gc_collections_in_timed_region": len(gc_pauses),
+                         "gc_longest_ms": max((ms for _, ms in gc_pauses), default=0.0),
+                         "gc_full_collections_ms": [round(ms, 3) for g, ms in gc_pauses if g == 2]},
         "verified": f"layers {check_layers} bit-exact vs oracle after the timed steps",
         "extras": extras,
     }
