@@ -141,9 +141,16 @@ def main() -> int:
     ap.add_argument("--run-length-sweep", action="store_true",
                     help="also time the pull of the same token count with block tables made of runs of exactly "
                          "1, 2, 4, ... consecutive blocks (both sides, source only, destination only)")
+    ap.add_argument("--locality-sweep", action="store_true",
+                    help="also time the pull of lone blocks whose queue neighbours are a fixed distance apart, and of lone "
+                         "blocks queued in address order of one or both sides")
     ap.add_argument("--size-sweep", action="store_true",
                     help="also time the pull of 1/8 ... 2x the configuration's token count (configurations 2 and 4), "
                          "the bandwidth-against-transfer-size curve of the paper's motivation")
+    ap.add_argument("--lone-blocks", action="store_true",
+                    help="replace the configuration's block tables by tables in which every block is alone on both sides")
+    ap.add_argument("--block-major", action="store_true",
+                    help="describe the same pool memory as [block][layer][K/V] pools")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
@@ -169,6 +176,22 @@ def main() -> int:
     kvd.lib()  # fail now if the library is missing
     torch.cuda.set_device(0)
     w = wl.CONFIGS[args.config]()
+    if args.lone_blocks or args.block_major:
+        # variants of a single-request configuration for diagnosis: the same pools and token count with every
+        # block alone on both sides, and/or the same memory described as [block][layer][K/V] pools
+        import dataclasses
+        assert len(w.requests) == 1, "--lone-blocks / --block-major are for the single-request configurations"
+        gs, gd, r = w.src, w.dst, w.requests[0]
+        name = w.name
+        if args.block_major:
+            gs, gd = dataclasses.replace(gs, block_major=True), dataclasses.replace(gd, block_major=True)
+            name += "-block-major"
+        if args.lone_blocks:
+            rng = np.random.default_rng(w.seed + 3000)
+            r = wl.Request(r.seq_len, wl.fixed_run_table(rng, gs.num_blocks, wl.blocks_for(r.seq_len, gs.block_tokens), 1),
+                           wl.fixed_run_table(rng, gd.num_blocks, wl.blocks_for(r.seq_len, gd.block_tokens), 1))
+            name += "-lone-blocks"
+        w = wl.Workload(name, gs, gd, [r], w.dtype, w.seed, w.layer_begin, w.layer_end)
     log(f"{w.name}: pools {w.src.total_bytes / 2**30:.2f} + {w.dst.total_bytes / 2**30:.2f} GiB, "
         f"{len(w.requests)} requests, {w.total_tokens} tokens")
     src = G.device_random_pool(w.src, w.dtype, w.seed)
@@ -494,6 +517,85 @@ def main() -> int:
                                                              "descriptors": y.plan.stats(sh)["num_descriptors"]}
                 y.close()
             extras["run_length_sweep"] = sweep
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
+        # where lone pieces lose their bandwidth: (a) every block alone, but queue neighbours a fixed distance apart
+        # (groups of `group` blocks, `distance` blocks between members), (b) the same block ids paired and queued
+        # so that one or both sides are swept in address order -- what the order of the queue is worth at best
+        if args.locality_sweep and len(w.requests) == 1 and not stats["relayout"]:
+            tokens = w.requests[0].seq_len
+            nblk = wl.blocks_for(tokens, w.src.block_tokens)
+            keep = kvd.KVD_PLAN_QUEUE_ORDER | kvd.KVD_PLAN_NO_COALESCE  # the queue as given, every block its own descriptor
+
+            def pull_pct(ts, td, flags=keep):
+                wr = wl.Workload(f"{w.name}-locality", w.src, w.dst,
+                                 [wl.Request(tokens, np.asarray(ts, np.int32), np.asarray(td, np.int32))],
+                                 w.dtype, w.seed, w.layer_begin, w.layer_end)
+                y = G.GpuTransfer(wr, src, dst, flags, stream=stream)
+                y.build()
+                y.plan.pull(sh)
+                us = min(timed(lambda: y.plan.pull(sh), 10) for _ in range(2))
+                y.close()
+                return {"pull_us": us, "pct_of_peak": 2 * payload / us / 1e3 / PEAK_HBM_GBPS * 100}
+
+            def spaced(rng, pool_blocks, group, distance):
+                span = 1
+                while span < group * distance + 2:
+                    span *= 2
+                slots = rng.permutation(pool_blocks // span)
+                ids = np.concatenate([sl * span + np.arange(group) * distance for sl in slots[:-(-nblk // group)]])
+                return ids[:nblk]
+            sweep = {}
+            for group in (2, 4):
+                for distance in (2, 3, 4, 8, 32):
+                    if (nblk // group + 1) * group * distance * 2 > w.src.num_blocks:
+                        continue
+                    rng = np.random.default_rng(w.seed + 4000)
+                    sweep[f"lone_blocks_in_groups_of_{group}_members_{distance}_blocks_apart"] = pull_pct(
+                        spaced(rng, w.src.num_blocks, group, distance), spaced(rng, w.dst.num_blocks, group, distance))
+            rng = np.random.default_rng(w.seed + 3000)
+            ts = wl.fixed_run_table(rng, w.src.num_blocks, nblk, 1)
+            td = wl.fixed_run_table(rng, w.dst.num_blocks, nblk, 1)
+            o_d, o_s = np.argsort(td), np.argsort(ts)
+            sweep["lone_blocks_queue_order"] = pull_pct(ts, td)
+            sweep["lone_blocks_grouped_by_2MiB_destination_region"] = pull_pct(ts, td, kvd.KVD_PLAN_NO_COALESCE)
+            sweep["lone_blocks_queue_sorted_by_destination"] = pull_pct(ts[o_d], td[o_d])
+            sweep["lone_blocks_queue_sorted_by_source"] = pull_pct(ts[o_s], td[o_s])
+            sweep["lone_blocks_both_sides_in_address_order"] = pull_pct(np.sort(ts), np.sort(td))
+            # the configuration's own block ids: as queued, and paired / queued in address order
+            r0 = w.requests[0]
+            cs, cd = np.asarray(r0.src_table[:nblk]), np.asarray(r0.dst_table[:nblk])
+            q = kvd.KVD_PLAN_QUEUE_ORDER
+            o_d = np.argsort(cd)
+            sweep["configured_tables_as_the_library_orders_them"] = pull_pct(cs, cd, 0)
+            sweep["configured_tables_queue_order"] = pull_pct(cs, cd, q)
+            sweep["configured_tables_queue_sorted_by_destination"] = pull_pct(cs[o_d], cd[o_d], q)
+            sweep["configured_tables_both_sides_in_address_order"] = pull_pct(np.sort(cs), np.sort(cd), q | kvd.KVD_PLAN_NO_COALESCE)
+            extras["locality_sweep"] = sweep
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
+        # re-layout plans: the configuration's own block ids, and the same ids with both sides swept in address order
+        if args.locality_sweep and len(w.requests) == 1 and stats["relayout"]:
+            r0 = w.requests[0]
+
+            def relayout_pct(ts, td):
+                wr = wl.Workload(f"{w.name}-locality", w.src, w.dst, [wl.Request(r0.seq_len, np.asarray(ts, np.int32), np.asarray(td, np.int32))],
+                                 w.dtype, w.seed, w.layer_begin, w.layer_end)
+                y = G.GpuTransfer(wr, src, dst, stream=stream)
+                y.build()
+                y.plan.pull(sh)
+                us = min(timed(lambda: y.plan.pull(sh), 10) for _ in range(2))
+                y.close()
+                return {"pull_us": us, "pct_of_peak": 2 * payload / us / 1e3 / PEAK_HBM_GBPS * 100}
+            extras["locality_sweep"] = {
+                "configured_tables": relayout_pct(r0.src_table, r0.dst_table),
+                "configured_tables_both_sides_in_address_order": relayout_pct(np.sort(r0.src_table), np.sort(r0.dst_table)),
+                "dense_identity_tables": relayout_pct(np.arange(len(r0.src_table)), np.arange(len(r0.dst_table))),
+            }
             x.plan.reset()
             x.build(batch)
             x.plan.pull(sh)

@@ -35,17 +35,32 @@ def run_and_compare(w: wl.Workload, src_host: np.ndarray, flags: int = 0):
     return x
 
 
+def _layer_slabs(g: wl.PoolGeometry, pool: torch.Tensor, layer: int) -> np.ndarray:
+    """One layer of a device pool on the host, as the bytes of a one-layer pool in [kv][block] order
+    (a plain slice for layer-major pools; gathered through torch's strided view otherwise)."""
+    if not g.block_major and not g.kv_adjacent:
+        nbytes = g.stride_layer * g.elem_bytes
+        return pool[layer * nbytes:(layer + 1) * nbytes].cpu().numpy()
+    tile = g.tile_elems * g.elem_bytes
+    if g.block_major:
+        v = pool.view(g.num_blocks, g.num_layers, 2, tile)[:, layer]   # [block][kv][tile]
+    else:
+        v = pool.view(g.num_layers, g.num_blocks, 2, tile)[layer]      # [block][kv][tile]
+    return v.permute(1, 0, 2).contiguous().view(-1).cpu().numpy()
+
+
 def compare_layer_with_oracle(w: wl.Workload, src: torch.Tensor, dst: torch.Tensor, layer: int):
-    """Oracle for one layer of a large workload: copies that layer's slabs to the host."""
-    gs, gd = w.src, w.dst
-    sb, db = gs.stride_layer * gs.elem_bytes, gd.stride_layer * gd.elem_bytes
-    src_host = src[layer * sb:(layer + 1) * sb].cpu().numpy()
-    got = dst[layer * db:(layer + 1) * db].cpu().numpy()
-    want = np.full(db // 2, wl.SENTINEL16, dtype=np.uint16).view(np.uint8)
+    """Oracle for one layer of a large workload: copies that layer's slabs to the host and hands
+    them to the oracle as a one-layer pool in [kv][block] order, addressed with that pool's own strides."""
+    g1s, g1d = (wl.PoolGeometry(1, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes, g.layout)
+                for g in (w.src, w.dst))
+    src_host = _layer_slabs(w.src, src, layer)
+    got = _layer_slabs(w.dst, dst, layer)
+    want = np.full(got.size // 2, wl.SENTINEL16, dtype=np.uint16).view(np.uint8)
     if w.layer_begin <= layer < w.layer_end:
-        s = tl.oracle_tensors(gs, src_host, first_layer=layer, num_layers=1)
-        d = tl.oracle_tensors(gd, want, first_layer=layer, num_layers=1)
+        s = tl.oracle_tensors(g1s, src_host)
+        d = tl.oracle_tensors(g1d, want)
         from oracle import kvd_oracle as orc
         for r in w.requests:
-            orc.pull(s, d, layer, layer + 1, r.src_table, r.dst_table, r.seq_len)
+            orc.pull(s, d, 0, 1, r.src_table, r.dst_table, r.seq_len)
     assert_bytes_equal(got, want, f"{w.name} layer {layer}")

@@ -1083,15 +1083,11 @@ def test_full_config2_block_major_with_every_block_alone():
     di = torch.from_numpy(r.dst_table[:n - 1].astype(np.int64)).cuda()
     for lo in range(0, n - 1, 128):
         assert torch.equal(dv[di[lo:lo + 128]], sv[si[lo:lo + 128]])
-    # oracle, element by element, on sampled layers: torch's strided view hands the layer over as a
-    # one-layer pool in [kv][block] order, which the oracle addresses with that pool's own strides
-    g1 = wl.PoolGeometry(1, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes, g.layout)
-    w1 = wl.Workload(w.name, g1, g1, w.requests, "bf16", 77)
-    for layer in (0, 13, 31):
+    # oracle, element by element, on every layer: torch's strided view hands the layer over as a one-layer
+    # pool in [kv][block] order, which the oracle addresses with that pool's own strides
+    for layer in range(g.num_layers):
         say(f"{w.name}: oracle on layer {layer}")
-        src_host = sv[:, layer].permute(1, 0, 2).contiguous().view(torch.uint8).view(-1).cpu().numpy()
-        got = dv[:, layer].permute(1, 0, 2).contiguous().view(torch.uint8).view(-1).cpu().numpy()
-        G.assert_bytes_equal(got, G.oracle_expected(w1, src_host), f"{w.name} layer {layer}")
+        G.compare_layer_with_oracle(w, src, dst, layer)
     x.close()
 
 
