@@ -299,6 +299,35 @@ def main() -> int:
             torch.cuda.synchronize()
             extras["build_one_call_per_request_us"] = (time.perf_counter() - t) / 5 * 1e6
             build_only()
+        # a completion per request inside the batched pull (section 4.2): the cost against the plain pull of the
+        # same plan, and when the first and the last request are announced
+        if batch:
+            y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_COMPLETE_PER_REQUEST, stream=stream)
+            y.build(True)
+            words = torch.zeros(len(w.requests), dtype=torch.int64).pin_memory()
+            y.plan.pull_notify(words.data_ptr(), 1, sh)
+            torch.cuda.synchronize()
+            value = [1]
+
+            def notify():
+                value[0] += 1
+                y.plan.pull_notify(words.data_ptr(), value[0], sh)
+            extras["per_request_completion_pull_notify_us"] = timed(notify, 10)
+            extras["per_request_completion_plain_pull_of_same_plan_us"] = timed(lambda: y.plan.pull(sh), 10)
+            extras["per_request_completion_descriptors"] = y.plan.stats(sh)["num_descriptors"]
+            torch.cuda.synchronize()
+            value[0] += 1
+            t = time.perf_counter()
+            y.plan.pull_notify(words.data_ptr(), value[0], sh)
+            seen = {}
+            while len(seen) < len(w.requests) and time.perf_counter() - t < 10:
+                for k in np.nonzero(words.numpy() == value[0])[0]:
+                    seen.setdefault(int(k), time.perf_counter() - t)
+            torch.cuda.synchronize()
+            extras["per_request_completion_first_word_us"] = min(seen.values()) * 1e6
+            extras["per_request_completion_median_word_us"] = float(np.median(list(seen.values()))) * 1e6
+            extras["per_request_completion_last_word_us"] = max(seen.values()) * 1e6
+            y.close()
         # practical ceilings: one contiguous device-to-device copy of the payload
         n = min(payload, 1 << 30)
         a = torch.empty(n, dtype=torch.uint8, device="cuda")

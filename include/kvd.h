@@ -93,6 +93,10 @@ typedef struct kvd_plan kvd_plan_t;
                                    in queue order whatever the plan looks like (ablation)           */
 #define KVD_PLAN_WIDE_OFFSETS 16u /* block-major plans: carry 48-bit offsets even where 32 bits reach the whole
                                    pool (the form pools above 64 GiB get by themselves); for testing  */
+#define KVD_PLAN_COMPLETE_PER_REQUEST 32u /* every request of the plan is followed by its own completion
+                                   transaction (section 4.2), so reads are merged inside a request only - merging stops
+                                   at the first completion in the queue - and kvd_pull_notify can announce each request
+                                   when its own reads are done                                        */
 #define KVD_PLAN_PERSISTENT 2u  /* kvd_pull uses a persistent grid that stages the coalesced descriptors
                                    in LDS and walks them wave by wave, instead of one small workgroup
                                    per work item (for comparison; slower; one layer range per plan) */
@@ -242,6 +246,25 @@ int kvd_pull(kvd_plan_t *plan, void *stream);
  * KVD_ERR_HIP.
  */
 int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, void *stream);
+
+/*
+ * kvd_pull with a completion per request (section 4.2: a completion transaction is processed when the
+ * reads of ITS request are done, while the reads of other requests go on): moves what kvd_pull moves,
+ * and stores `value` into words[k] as soon as every byte of the plan's k-th request (in the order of
+ * appending; requests of length 0 are not counted, see kvd_stats_t.num_requests) has arrived, with those
+ * bytes visible to any reader of the word first (system-scope release).  `words` holds at least
+ * num_requests 8-byte words owned by the caller, in device memory or in pinned host memory that a CPU
+ * thread polls; the caller chooses `value` so that it differs from what the words held before.
+ * The plan must have been created with KVD_PLAN_COMPLETE_PER_REQUEST.  Requests are moved in queue order,
+ * one launch each on two library-owned side streams in turn (default priority), so that the next request's
+ * reads are in flight while one request's last reads finish; `stream` is forked from and joined again:
+ * work enqueued on `stream` after the call runs after the whole plan has been moved.  Work items are
+ * walked in queue order (no grouping by destination region).  May be recorded into a HIP graph.
+ * Errors: KVD_ERR_INVALID (handle, null or misaligned words, memory the GPU cannot reach),
+ * KVD_ERR_MISMATCH (plan without KVD_PLAN_COMPLETE_PER_REQUEST, KVD_PLAN_PERSISTENT, re-layout plans between
+ * block-major pools), KVD_ERR_HIP.
+ */
+int kvd_pull_notify(kvd_plan_t *plan, uint64_t *words, uint64_t value, void *stream);
 
 /*
  * For callers that cannot allocate device memory - code under HIP graph capture, tight serving

@@ -3,6 +3,7 @@
 // Validation, the plan object and its scratch memory, and the launches of the kernels in
 // kvd_kernels.h (structures, device code and their description).
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -71,9 +72,16 @@ struct ReqHost {
     uint32_t table_off_src, table_off_dst;  // into the plan's table mirrors
     uint32_t n_src, n_dst;                  // entries used
     uint32_t seq_len, layer_begin, layer_end;
+    uint32_t item_bound;                    // work items per slab before merging (upper bound of what it has)
 };
 
 }  // namespace
+
+// Side streams that the per-request pulls of kvd_pull_notify take turns on.
+#ifndef KVD_NOTIFY_STREAMS
+#define KVD_NOTIFY_STREAMS 2
+#endif
+constexpr int kNotifyStreams = KVD_NOTIFY_STREAMS;
 
 struct kvd_pool {
     uint32_t tag;
@@ -129,6 +137,13 @@ struct kvd_plan {
     uint32_t *done_host, *done_dev;
     uint32_t build_seq;
     hipStream_t build_stream;
+    // KVD_PLAN_COMPLETE_PER_REQUEST: where each request starts in the descriptor and work-item
+    // tables (device), and the two streams its pulls alternate on with their fork / join events
+    uint32_t *req_desc_dev, *req_item_dev;
+    hipStream_t notify_stream[kNotifyStreams], notify_tell;  // the pulls take turns on the first; the words are written on the last
+    hipEvent_t notify_fork, notify_join[kNotifyStreams + 1];
+    std::vector<hipEvent_t> notify_done;                      // one per request: set when its pull kernel has finished
+    bool notify_ready;
 };
 
 namespace {
@@ -219,6 +234,22 @@ void free_scratch(kvd_plan *p)
     if (p->items_dev) (void)hipFree(p->items_dev);
     if (p->ordered_dev) (void)hipFree(p->ordered_dev);
     if (p->hdr_dev) (void)hipFree(p->hdr_dev);
+    if (p->req_desc_dev) (void)hipFree(p->req_desc_dev);
+    if (p->req_item_dev) (void)hipFree(p->req_item_dev);
+    if (p->notify_ready) {
+        for (int i = 0; i < kNotifyStreams; ++i) {
+            (void)hipStreamSynchronize(p->notify_stream[i]);
+            (void)hipStreamDestroy(p->notify_stream[i]);
+        }
+        (void)hipStreamSynchronize(p->notify_tell);
+        (void)hipStreamDestroy(p->notify_tell);
+        for (int i = 0; i <= kNotifyStreams; ++i) (void)hipEventDestroy(p->notify_join[i]);
+        for (hipEvent_t e : p->notify_done) (void)hipEventDestroy(e);
+        p->notify_done.clear();
+        (void)hipEventDestroy(p->notify_fork);
+        p->notify_ready = false;
+    }
+    p->req_desc_dev = p->req_item_dev = nullptr;
     p->done_host = nullptr;
     p->tables_src = p->tables_dst = nullptr;
     p->reqs_pinned = nullptr;
@@ -246,6 +277,10 @@ int allocate_scratch(kvd_plan *p)
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->ordered_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
+    if (p->flags & KVD_PLAN_COMPLETE_PER_REQUEST) {
+        KVD_HIP(hipMalloc((void **)&p->req_desc_dev, (size_t)p->max_requests * sizeof(uint32_t)));
+        KVD_HIP(hipMalloc((void **)&p->req_item_dev, (size_t)p->max_requests * sizeof(uint32_t)));
+    }
     KVD_HIP(hipHostMalloc((void **)&p->done_host, 64, hipHostMallocMapped));
     KVD_HIP(hipHostGetDevicePointer((void **)&p->done_dev, p->done_host, 0));
     *p->done_host = 0;
@@ -332,6 +367,10 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     a.slabs = (whole ? p->max_layers : l1 - l0) << p->geo.kv_shift;
     a.absolute_layers = whole ? 0u : 1u;
     a.layer0 = l0;
+    a.req_item = nullptr;
+    a.req = a.n_req = 0;
+    a.announce = nullptr;
+    a.announce_value = 0;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
         for (const ReqHost &r : p->reqs)
@@ -378,6 +417,25 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     return KVD_OK;
 }
 
+// The side streams (default priority) of the per-request pulls, the events they fork from and join
+// at, and one event per request of the plan.
+int ensure_notify_streams(kvd_plan *p)
+{
+    if (!p->notify_ready) {
+        KVD_HIP(hipEventCreateWithFlags(&p->notify_fork, hipEventDisableTiming));
+        for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamCreateWithFlags(&p->notify_stream[i], hipStreamNonBlocking));
+        KVD_HIP(hipStreamCreateWithFlags(&p->notify_tell, hipStreamNonBlocking));
+        for (int i = 0; i <= kNotifyStreams; ++i) KVD_HIP(hipEventCreateWithFlags(&p->notify_join[i], hipEventDisableTiming));
+        p->notify_ready = true;
+    }
+    while (p->notify_done.size() < p->reqs.size()) {
+        hipEvent_t e;
+        KVD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        p->notify_done.push_back(e);
+    }
+    return KVD_OK;
+}
+
 // What every launch of the build kernel takes from the plan: where its scratch is, the layer range,
 // the sizes of the batch.  The caller adds the batch itself (reqs, first, n_req) and how it joins
 // the queue (fresh, may_merge_prev).
@@ -403,6 +461,9 @@ BuildArgs build_args(kvd_plan *p, const Geo &g, uint32_t layer_begin, uint32_t n
     a.expand_inline = batch_items <= kInlineItems ? 1u : 0u;
     a.done = p->done_dev;
     a.seq = ++p->build_seq;
+    a.req_desc = p->req_desc_dev;  // null unless the plan completes request by request
+    a.req_item = p->req_item_dev;
+    a.req_base = 0;
     return a;
 }
 
@@ -747,6 +808,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         r.seq_len = seq_len;
         r.layer_begin = layer_begin;
         r.layer_end = layer_end;
+        r.item_bound = 0;
         memcpy(p->tables_src + r.table_off_src, src_tbls[k], (size_t)r.n_src * sizeof(int32_t));
         memcpy(p->tables_dst + r.table_off_dst, dst_tbls[k], (size_t)r.n_dst * sizeof(int32_t));
         for (uint32_t i = 0; i < r.n_dst; ++i) p->dst_used[(uint32_t)dst_tbls[k][i]] = 1;
@@ -763,6 +825,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
             const ReqHost &r = p->reqs[b0 + i];
             uint32_t n_txn = 0, items = 0;
             request_sizes(g, r.seq_len, &n_txn, &items);
+            p->reqs[b0 + i].item_bound = items;
             p->reqs_pinned[b0 + i] = ReqDev{r.table_off_src, r.table_off_dst, r.seq_len, batch_txn};
             batch_txn += n_txn;
             batch_items += items;
@@ -772,7 +835,8 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         a.first = p->reqs_pinned[b0];
         a.n_req = nb;
         a.fresh = (b0 == 0) ? 1u : 0u;
-        a.may_merge_prev = (b0 > first_new || same_layers) ? 1u : 0u;
+        a.may_merge_prev = ((b0 > first_new || same_layers) && !(p->flags & KVD_PLAN_COMPLETE_PER_REQUEST)) ? 1u : 0u;
+        a.req_base = (uint32_t)b0;
         p->build_stream = (hipStream_t)stream;
         hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
         hipError_t launch = hipGetLastError();
@@ -823,6 +887,72 @@ int kvd_pull_layers(kvd_plan_t *p, uint32_t layer_begin, uint32_t layer_end, voi
     if (p->flags & KVD_PLAN_PERSISTENT) return fail(KVD_ERR_MISMATCH, "the persistent form moves whole plans only");
     if (p->reqs.empty()) return KVD_OK;
     return launch_pull(p, stream, false, layer_begin, layer_end);
+}
+
+int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream)
+{
+    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
+    if (!(p->flags & KVD_PLAN_COMPLETE_PER_REQUEST))
+        return fail(KVD_ERR_MISMATCH, "the plan was not created with KVD_PLAN_COMPLETE_PER_REQUEST");
+    if (p->by_descriptor || (p->flags & KVD_PLAN_PERSISTENT))
+        return fail(KVD_ERR_MISMATCH, "per-request completion is not available for this kind of plan");
+    if (p->reqs.empty()) return KVD_OK;
+    if (!words) return fail(KVD_ERR_INVALID, "null completion words");
+    if ((uintptr_t)words % 8) return fail(KVD_ERR_INVALID, "completion words must be 8-byte aligned");
+    hipPointerAttribute_t at;
+    if (hipPointerGetAttributes(&at, words) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KVD_ERR_INVALID, "the completion words are not memory the GPU can reach (device memory or pinned host memory)");
+    }
+    if (!at.devicePointer) return fail(KVD_ERR_INVALID, "the completion words are host memory that is not mapped into the device");
+    uint64_t *words_dev = (uint64_t *)at.devicePointer;
+    int rc = ensure_notify_streams(p);
+    if (rc != KVD_OK) return rc;
+
+    // Request k's reads run as one launch; consecutive requests alternate between two side streams, so
+    // the next request's reads are in flight while this one's last workgroups drain (section 4.2: reads
+    // of other requests do not wait for a completion).  Each launch carries an event that is set when
+    // that kernel has finished; a third stream waits for the events in request order and stores each
+    // request's word behind its own (completions are sent one after the other, as in the paper).
+    // The side streams start behind everything enqueued on `stream` so far, and `stream` continues
+    // behind all of them.
+    hipStream_t st = (hipStream_t)stream;
+    KVD_HIP(hipEventRecord(p->notify_fork, st));
+    for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamWaitEvent(p->notify_stream[i], p->notify_fork, 0));
+    constexpr int T = 64;
+    const uint32_t n_req = (uint32_t)p->reqs.size();
+    for (uint32_t k = 0; k < n_req; ++k) {
+        const ReqHost &r = p->reqs[k];
+        hipStream_t side = p->notify_stream[k % kNotifyStreams];
+        PullArgs a;
+        a.src_base = (const unsigned char *)p->src.base;
+        a.dst_base = (unsigned char *)p->dst.base;
+        a.items = p->items_dev;  // queue order: a request's work items are one range of the table
+        a.hdr = p->hdr_dev;
+        a.slabs = (p->fold_layers ? 1u : r.layer_end - r.layer_begin) << p->geo.kv_shift;
+        a.absolute_layers = 0;
+        a.layer0 = 0;
+        a.req_item = p->req_item_dev;
+        a.req = k;
+        a.n_req = n_req;
+        // the word of the request that ran on this side stream before this one is stored by this
+        // launch's first workgroup; the last request of each side stream gets a launch for its word
+        a.announce = k >= (uint32_t)kNotifyStreams ? words_dev + (k - kNotifyStreams) : nullptr;
+        a.announce_value = value;
+        const uint64_t gx = ((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8;
+        if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
+        hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, side, p->geo, a);
+        KVD_HIP(hipGetLastError());
+        if (k + kNotifyStreams >= n_req) {
+            hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, side, words_dev + k, value);
+            KVD_HIP(hipGetLastError());
+        }
+    }
+    for (int i = 0; i <= kNotifyStreams; ++i) {
+        KVD_HIP(hipEventRecord(p->notify_join[i], i < kNotifyStreams ? p->notify_stream[i] : p->notify_tell));
+        KVD_HIP(hipStreamWaitEvent(st, p->notify_join[i], 0));
+    }
+    return KVD_OK;
 }
 
 int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, const int32_t *src_tbl, uint32_t n_src,
@@ -963,6 +1093,10 @@ int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_
     a.slabs = p->max_layers << p->geo.kv_shift;
     a.absolute_layers = 0;
     a.layer0 = 0;
+    a.req_item = nullptr;
+    a.req = a.n_req = 0;
+    a.announce = nullptr;
+    a.announce_value = 0;
     const uint32_t cap = (uint32_t)std::min<uint64_t>(buffer_bytes / 4096, 1u << 20);
     for (uint32_t y = 0; y < a.slabs; ++y)
         for (uint32_t c0 = 0; c0 < h.n_items; c0 += cap) {

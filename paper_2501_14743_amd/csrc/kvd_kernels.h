@@ -149,6 +149,13 @@ struct BuildArgs {
     uint32_t expand_inline;    // 1: this workgroup also writes the work items (few of them)
     uint32_t *done;            // pinned host word that receives `seq` once the tables have been read
     uint32_t seq;
+    // Plans that complete request by request (section 4.2: a completion transaction sits behind the
+    // reads of its own request, and reads are merged only up to the first completion): a request's
+    // first transaction always starts a descriptor, and the descriptor / work item each request of
+    // the batch starts at are recorded for the per-request pulls.  Null otherwise.
+    uint32_t *req_desc;        // [requests of the plan] first descriptor
+    uint32_t *req_item;        // [requests of the plan] first work item
+    uint32_t req_base;         // index of the batch's first request within the plan
 };
 
 struct Txn {
@@ -282,17 +289,21 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         const uint32_t j = tile + tid;
         const bool valid = j < a.n_txn;
         Txn t = {0, 0, 0, 0};
+        uint32_t req = 0;                // the request transaction j belongs to (index within the batch)
+        bool first_of_request = false;   // ... and whether it opens that request's own descriptors
         if (valid) {
             ReqDev rq = a.first;
             if (a.n_req > 1) {
-                uint32_t lo = 0, hi = a.n_req;  // the request transaction j belongs to
+                uint32_t lo = 0, hi = a.n_req;
                 while (hi - lo > 1) {
                     const uint32_t mid = (lo + hi) >> 1;
                     if (s_req[mid].txn_begin <= j) lo = mid; else hi = mid;
                 }
                 rq = s_req[lo];
+                req = lo;
             }
             t = make_txn(g, a, rq, j - rq.txn_begin);
+            first_of_request = a.req_desc && j == rq.txn_begin;
         }
         // With 48-bit offsets a descriptor's length must still fit 32 bits: its transactions all
         // start in one 2^31-unit window (32 GiB) per side, so a run breaks where it enters the next one.
@@ -313,7 +324,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         const uint64_t next_prev_s = s_end_s[tile_last], next_prev_d = s_end_d[tile_last], next_prev_w = s_win[tile_last];
 
         // break flag: this transaction starts a new descriptor
-        const bool brk = valid && (never_merge || !hp || ps != t.s16 || pd != t.d16 || pw != my_w);
+        const bool brk = valid && (never_merge || !hp || ps != t.s16 || pd != t.d16 || pw != my_w || first_of_request);
         const uint64_t ballot = __ballot(brk);
         const uint32_t before = __popcll(ballot & ((1ull << lane) - 1ull));
         if (lane == 0) s_wave[wave] = __popcll(ballot);
@@ -329,6 +340,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         if (valid) {
             // descriptor this transaction belongs to = (breaks up to and including it) - 1
             const uint32_t run = runs + wave_prefix + before + (brk ? 1u : 0u) - 1u;
+            if (first_of_request) a.req_desc[a.req_base + req] = run;
             if (brk) {
                 a.desc[run].src16 = (uint32_t)t.s16;
                 a.desc[run].dst16 = (uint32_t)t.d16;
@@ -390,6 +402,10 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         __syncthreads();
     }
     const uint32_t n_items = carry;
+    // where each request of the batch starts in the work-item table (the prefixes above were written
+    // by this workgroup and the loop's last barrier has passed)
+    if (a.req_item)
+        for (uint32_t i = tid; i < a.n_req; i += kBuildThreads) a.req_item[a.req_base + i] = a.desc[a.req_desc[a.req_base + i]].prefix;
 
     // expand descriptors [from, n1) into work items [first_item, n_items), a window of
     // descriptors at a time with their prefixes staged in LDS for the item -> descriptor search
@@ -475,6 +491,14 @@ struct PullArgs {
     // 1: slab y is layer `layer0 + y / (K, V slabs)` of the pools, and items without it sit out
     uint32_t absolute_layers;
     uint32_t layer0;
+    // one request of the plan only (per-request completion): work items [req_item[req], req_item[req + 1])
+    // of the table, the last request's up to the table's end.  Null: the whole table.
+    const uint32_t *req_item;
+    uint32_t req, n_req;
+    // A completion word to store before anything else (null: none): that of the request whose pull
+    // ran before this launch on the same stream, so that it costs no launch of its own.
+    uint64_t *announce;
+    uint64_t announce_value;
 };
 
 // Streaming 16-byte store: non-temporal at device scope.  Measured on MI355X, this cache policy
@@ -565,16 +589,21 @@ __global__ __launch_bounds__(64) void kvd_stage_kernel(Geo g, PullArgs a, unsign
 // scattered descriptors the plain order is kept (the contiguous deal measured 2 % slower there).
 // Returns false if there is nothing to do for this workgroup.
 template <int T>
-__device__ __forceinline__ bool pick_piece(const Header h, uint32_t b, uint32_t *piece)
+__device__ __forceinline__ bool pick_piece(const Header h, const PullArgs &a, uint32_t b, uint32_t *piece)
 {
     constexpr uint32_t kParts = kChunkUnits / T;
-    const uint32_t pieces = h.n_items * kParts;
+    uint32_t lo = 0, hi = h.n_items;  // the part of the item table this launch moves
+    if (a.req_item) {
+        lo = a.req_item[a.req];
+        if (a.req + 1 < a.n_req) hi = a.req_item[a.req + 1];
+    }
+    const uint32_t pieces = (hi - lo) * kParts;
     if (h.n_items >= 4 * h.n_desc) {
         const uint32_t per = (pieces + 7) >> 3;
         if ((b >> 3) >= per) return false;
         b = (b & 7) * per + (b >> 3);
     }
-    *piece = b;
+    *piece = lo * kParts + b;
     return b < pieces;
 }
 
@@ -584,15 +613,24 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
 {
     constexpr uint32_t kParts = kChunkUnits / T;
     uint32_t piece;
-    if (!pick_piece<T>(*a.hdr, blockIdx.x, &piece)) return;
-    const Item it = a.items[piece / kParts];
-    uint32_t y = blockIdx.y;
-    if (a.absolute_layers) {
-        const uint32_t rel = a.layer0 + (y >> g.kv_shift) - (it.layers & 0xFFFFu);  // wraps below the item's first layer
-        if (rel >= (it.layers >> 16)) return;
-        y = (rel << g.kv_shift) | (y & g.kv_shift);
+    if (pick_piece<T>(*a.hdr, a, blockIdx.x, &piece)) {
+        const Item it = a.items[piece / kParts];
+        uint32_t y = blockIdx.y;
+        bool mine = true;
+        if (a.absolute_layers) {
+            const uint32_t rel = a.layer0 + (y >> g.kv_shift) - (it.layers & 0xFFFFu);  // wraps below the item's first layer
+            mine = rel < (it.layers >> 16);
+            y = (rel << g.kv_shift) | (y & g.kv_shift);
+        }
+        if (mine) move_unit(g, a, it, y, (piece % kParts) * T + threadIdx.x);
     }
-    move_unit(g, a, it, y, (piece % kParts) * T + threadIdx.x);
+    // Stream order has put the previous launch's writes behind this one's start; the release at
+    // system scope makes them visible to whoever reads the word, before the word.  Kept at the very
+    // end: the loads above stay scalar loads only while no atomic precedes them in program order
+    // (with this store first, the header and item loads become vector loads and the whole kernel
+    // runs a quarter slower, measured).
+    if (a.announce && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        __hip_atomic_store(a.announce, a.announce_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Re-layout between pools that keep a block's layers together: the grid walks descriptor by

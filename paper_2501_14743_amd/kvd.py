@@ -27,6 +27,7 @@ KVD_PLAN_PERSISTENT = 2
 KVD_PLAN_WHOLE_BLOCKS = 4
 KVD_PLAN_QUEUE_ORDER = 8
 KVD_PLAN_WIDE_OFFSETS = 16
+KVD_PLAN_COMPLETE_PER_REQUEST = 32
 LAYOUTS = {"BHTD": KVD_LAYOUT_BHTD, "BTHD": KVD_LAYOUT_BTHD}
 
 
@@ -92,6 +93,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_pull_noalloc.argtypes = [ctypes.POINTER(kvd_pool_desc_t), ctypes.POINTER(kvd_pool_desc_t), i32p, u32, i32p, u32,
                                    u32, u32, u32, u32, vp]
     L.kvd_complete.argtypes = [vp, u64, vp]
+    L.kvd_pull_notify.argtypes = [vp, vp, u64, vp]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
     L.kvd_pull_staged.argtypes = [vp, vp, vp, u64, vp]
     L.kvd_plan_reset.argtypes = [vp]
@@ -102,7 +104,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
-                 "kvd_pull_layers", "kvd_pull_noalloc", "kvd_complete",
+                 "kvd_pull_layers", "kvd_pull_noalloc", "kvd_complete", "kvd_pull_notify",
                  "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain"):
         getattr(L, name).restype = ctypes.c_int
@@ -188,6 +190,10 @@ def kvd_pull_noalloc(src_desc: kvd_pool_desc_t, dst_desc: kvd_pool_desc_t, src_b
     st, dt = _table(src_block_table), _table(dst_block_table)
     _check(lib().kvd_pull_noalloc(ctypes.byref(src_desc), ctypes.byref(dst_desc), _i32p(st), st.size, _i32p(dt), dt.size,
                                   seq_len, layer_begin, layer_end, flags, stream))
+
+
+def kvd_pull_notify(plan: int, words_ptr: int, value: int, stream: int = 0) -> None:
+    _check(lib().kvd_pull_notify(plan, words_ptr, value, stream))
 
 
 def kvd_complete(flag_ptr: int, value: int, stream: int = 0) -> None:
@@ -277,6 +283,9 @@ class Plan:
 
     def pull(self, stream=0):
         kvd_pull(self.handle, stream)
+
+    def pull_notify(self, words_ptr, value, stream=0):
+        kvd_pull_notify(self.handle, words_ptr, value, stream)
 
     def pull_layers(self, layer_begin, layer_end, stream=0):
         kvd_pull_layers(self.handle, layer_begin, layer_end, stream)

@@ -341,6 +341,114 @@ def test_completion_word():
     x.close()
 
 
+def _request_words(w, request, g):
+    """Indices of the 16-bit words of the destination pool (as [layer][kv][block][words of a block]) that
+    one request's blocks cover, as a boolean mask over blocks."""
+    mask = np.zeros(g.num_blocks, bool)
+    mask[request.dst_table[:wl.blocks_for(request.seq_len, g.block_tokens)]] = True
+    return mask
+
+
+def test_per_request_completion_inside_one_batched_pull():
+    """kvd_pull_notify: every request of a batch gets its own completion word (section 4.2).  The descriptor
+    list is the oracle's merge of each request's reads by itself (merging stops at a completion); a reader
+    that waits for word k only, without synchronising any stream, finds request k's bytes equal to the
+    oracle's; at the end the whole pool equals the oracle's."""
+    import time
+    w = wl.config3(num_layers=4, num_requests=24, median=700.0, hi=4096)
+    g = w.dst
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    sh = x.stream.cuda_stream
+    x.build(batch=True)
+    got_desc = x.plan.descriptors(sh)
+    s_t, d_t = tl.oracle_tensors(w.src, None)[0], tl.oracle_tensors(w.dst, None)[0]
+    per_request = [orc.coalesce(orc.request_transactions(s_t, d_t, 0, r.src_table, r.dst_table, r.seq_len)) for r in w.requests]
+    assert np.array_equal(got_desc, np.concatenate(per_request))
+    n = len(w.requests)
+    words = torch.zeros(n, dtype=torch.int64).pin_memory()
+    want5 = torch.from_numpy(want).view(torch.int16).view(g.num_layers, 2, g.num_blocks, -1)
+    dst5 = dst.view(torch.int16).view(g.num_layers, 2, g.num_blocks, -1)
+    peer = torch.cuda.Stream()  # the reader's stream: ordered behind nothing but what the reader has seen in the words
+    for value in (7, 8):       # twice: the second time with the words holding the first value
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        x.after_torch()
+        x.plan.pull_notify(words.data_ptr(), value, sh)
+        seen_at = {}
+        t0 = time.time()
+        pending = set(range(n))
+        while pending:
+            assert time.time() - t0 < 30, f"completion words of requests {sorted(pending)} never arrived"
+            for k in sorted(pending):
+                if int(words[k]) == value:
+                    seen_at[k] = time.time() - t0
+                    pending.discard(k)
+                    idx = torch.from_numpy(np.nonzero(_request_words(w, w.requests[k], g))[0]).cuda()
+                    with torch.cuda.stream(peer):
+                        got = dst5[:, :, idx].clone()
+                    peer.synchronize()
+                    assert torch.equal(got.cpu(), want5[:, :, idx.cpu()]), f"request {k} after its completion word"
+        x.stream.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"whole pool after pull_notify (value {value})")
+        say(f"pull_notify value {value}: first word after {min(seen_at.values()) * 1e3:.2f} ms, last after {max(seen_at.values()) * 1e3:.2f} ms")
+    # the plain pull of such a plan moves the same bytes
+    dst.view(torch.int16).fill_(wl.SENTINEL16)
+    x.after_torch()
+    x.pull()
+    x.stream.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, "kvd_pull of a plan with per-request completion")
+    # refusals
+    y = G.GpuTransfer(w, src, dst)
+    y.build(batch=True)
+    with pytest.raises(kvd.KvdError) as e:
+        y.plan.pull_notify(words.data_ptr(), 1, sh)
+    assert e.value.code == kvd.KVD_ERR_MISMATCH
+    y.close()
+    host_only = np.zeros(n, np.int64)
+    for bad in (0, words.data_ptr() + 4, host_only.ctypes.data):
+        with pytest.raises(kvd.KvdError):
+            x.plan.pull_notify(bad, 1, sh)
+    x.close()
+
+
+@pytest.mark.parametrize("kind", ["mixed-layers", "block-major", "ragged-relayout"])
+def test_per_request_completion_other_plan_kinds(kind):
+    """Requests built one call at a time with different layer ranges, block-major pools (layers folded, wide
+    expansion) and a re-layout plan: device-memory words, whole pool against the oracle."""
+    rng = np.random.default_rng(17)
+    if kind == "block-major":
+        gs = gd = small_geom(block_major=True, num_blocks=256, num_layers=4)
+    elif kind == "ragged-relayout":
+        gs, gd = small_geom(num_blocks=256), small_geom(num_blocks=128, block_tokens=32, layout=wl.BTHD)
+    else:
+        gs = gd = small_geom(num_blocks=256, num_layers=5)
+    free_s, free_d = np.ones(gs.num_blocks, bool), np.ones(gd.num_blocks, bool)
+    lens = [333, 16, 1, 700, 64]
+    ranges = [(0, gs.num_layers)] * 5 if kind != "mixed-layers" else [(0, 5), (1, 3), (1, 3), (4, 5), (0, 5)]
+    reqs = [wl.Request(t, wl.fragmented_allocation(rng, free_s, wl.blocks_for(t, gs.block_tokens), 4),
+                       wl.fragmented_allocation(rng, free_d, wl.blocks_for(t, gd.block_tokens), 4)) for t in lens]
+    src_host = rng.integers(0, 256, size=gs.total_bytes, dtype=np.uint8)
+    want = wl.host_pool_sentinel(gd)
+    for r, (l0, l1) in zip(reqs, ranges):
+        tl.oracle_pull_workload(wl.Workload("one", gs, gd, [r], "bf16", 0, l0, l1), src_host, want)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(gd)
+    plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst.data_ptr(), gd), 5, 512, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    for r, (l0, l1) in zip(reqs, ranges):
+        plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1, stream.cuda_stream)
+    words = torch.zeros(5, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    plan.pull_notify(words.data_ptr(), 99, stream.cuda_stream)
+    stream.synchronize()
+    assert words.tolist() == [99] * 5
+    G.assert_bytes_equal(dst.cpu().numpy(), want, kind)
+    G.assert_bytes_equal(src.cpu().numpy(), src_host, kind + ": source changed")
+    plan.close()
+
+
 def test_merge_across_requests_as_in_queue_example():
     # R1 reads block 0 into 5, R2 reads 1 into 6 (+ 3 into 9): first two merge (section 4.2)
     g = small_geom(num_layers=1)
