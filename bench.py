@@ -151,6 +151,9 @@ def main() -> int:
                     help="replace the configuration's block tables by tables in which every block is alone on both sides")
     ap.add_argument("--block-major", action="store_true",
                     help="describe the same pool memory as [block][layer][K/V] pools")
+    ap.add_argument("--stream-probes", action="store_true",
+                    help="also time read-only, write-only and copy streams over plain 1 GiB buffers, dispatched in address "
+                         "order and from a persistent grid (the measurements behind the pull kernel's design)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
@@ -637,6 +640,30 @@ def main() -> int:
             torch.cuda.synchronize()
             extras["blockwise_memcpy_us"] = (time.perf_counter() - t) * 1e6
         log(f"extras: {extras}")
+
+    if args.stream_probes:
+        # what the memory system gives a read stream, a write stream and a copy on plain 1 GiB buffers, one access per
+        # lane with the workgroups dispatched in address order against a persistent grid striding over the buffer
+        n = 1 << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        a.view(torch.int16).fill_(0x3C00)
+        probes = {}
+        for mode in kvd.PROBE_MODES:
+            kvd.kvd_stream_probe(b.data_ptr(), a.data_ptr(), n, mode, sh)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                kvd.kvd_stream_probe(b.data_ptr(), a.data_ptr(), n, mode, sh)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / 10 * 1e3
+            moved = (2 if mode.startswith("copy") else 1) * n
+            probes[mode] = {"us": us, "GBps": moved / us / 1e3, "pct_of_peak": moved / us / 1e3 / PEAK_HBM_GBPS * 100}
+        extras["stream_probes_1GiB"] = probes
+        log(f"stream probes: { {k: round(v['GBps']) for k, v in probes.items()} }")
+        del a, b
 
     if args.copy_calibration:
         n = 1 << 30

@@ -352,6 +352,23 @@ int kvd_plan_get_descriptors(kvd_plan_t *plan, void *stream, kvd_span_t *spans,
  */
 int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream);
 
+/*
+ * Calibration, not the product path: one pass over plain buffers of `bytes` bytes (a multiple of 4096;
+ * DEVICE pointers, 16-byte aligned) with the pull kernel's access width and cache policies.  `mode`
+ * selects a copy, a read-only or a write-only stream, each either with one access per lane and the
+ * workgroups handed out by the hardware dispatcher in address order, or with a fixed grid of resident
+ * workgroups striding over the buffer (the persistent form).  Shows what the memory system gives each
+ * kind of stream, next to which the pull kernel's design is justified.  The write-only forms fill `dst`
+ * with a constant; the read-only forms leave both buffers unchanged.
+ */
+#define KVD_PROBE_COPY 0u
+#define KVD_PROBE_READ 1u
+#define KVD_PROBE_WRITE 2u
+#define KVD_PROBE_COPY_PERSISTENT 3u
+#define KVD_PROBE_READ_PERSISTENT 4u
+#define KVD_PROBE_WRITE_PERSISTENT 5u
+int kvd_stream_probe(void *dst, const void *src, uint64_t bytes, uint32_t mode, void *stream);
+
 /* Release a pool or a plan (NULL is allowed).  Frees the plan's own scratch, never pool memory.
  * The library keeps a list of the handles it has given out: a pointer that is not on it (released
  * before, or never a handle) is ignored here without being read, and refused with KVD_ERR_INVALID

@@ -1227,6 +1227,35 @@ int kvd_copy_plain(void *dst, const void *src, uint64_t bytes, void *stream)
     return KVD_OK;
 }
 
+int kvd_stream_probe(void *dst, const void *src, uint64_t bytes, uint32_t mode, void *stream)
+{
+    if (!dst || !src) return fail(KVD_ERR_INVALID, "null pointer");
+    if ((bytes % 4096) || bytes == 0 || ((uintptr_t)dst % 16) || ((uintptr_t)src % 16))
+        return fail(KVD_ERR_INVALID, "size must be a positive multiple of 4096 bytes and the pointers multiples of 16");
+    if (mode > 5) return fail(KVD_ERR_INVALID, "mode %u: 0..5", mode);
+    const uint64_t units = bytes / 16, grid = units / 256;
+    if (grid >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "buffer too large for one launch");
+    int dev = 0;
+    hipDeviceProp_t prop;
+    KVD_HIP(hipGetDevice(&dev));
+    KVD_HIP(hipGetDeviceProperties(&prop, dev));
+    const uint32_t resident = (uint32_t)std::min<uint64_t>(grid, (uint64_t)prop.multiProcessorCount * 8);  // 8 workgroups of 4 waves per CU
+    const u32x4 fill = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    u32x4 *d = (u32x4 *)dst;
+    const u32x4 *s = (const u32x4 *)src;
+    hipStream_t st = (hipStream_t)stream;
+    switch (mode) {
+    case KVD_PROBE_COPY: hipLaunchKernelGGL((kvd_probe_kernel<true, true, true>), dim3((uint32_t)grid), dim3(256), 0, st, d, s, units, fill); break;
+    case KVD_PROBE_READ: hipLaunchKernelGGL((kvd_probe_kernel<true, false, true>), dim3((uint32_t)grid), dim3(256), 0, st, d, s, units, fill); break;
+    case KVD_PROBE_WRITE: hipLaunchKernelGGL((kvd_probe_kernel<false, true, true>), dim3((uint32_t)grid), dim3(256), 0, st, d, s, units, fill); break;
+    case KVD_PROBE_COPY_PERSISTENT: hipLaunchKernelGGL((kvd_probe_kernel<true, true, false>), dim3(resident), dim3(256), 0, st, d, s, units, fill); break;
+    case KVD_PROBE_READ_PERSISTENT: hipLaunchKernelGGL((kvd_probe_kernel<true, false, false>), dim3(resident), dim3(256), 0, st, d, s, units, fill); break;
+    default: hipLaunchKernelGGL((kvd_probe_kernel<false, true, false>), dim3(resident), dim3(256), 0, st, d, s, units, fill); break;
+    }
+    KVD_HIP(hipGetLastError());
+    return KVD_OK;
+}
+
 void kvd_free(void *handle)
 {
     // only a handle that is still on the list of live ones is touched: a second release of the

@@ -20,6 +20,7 @@
 //                      comparison).
 //   kvd_stage_kernel   gather into / scatter out of a staging buffer (message-style baseline).
 //   kvd_copy_kernel    plain streaming copy (counter calibration / practical ceiling).
+//   kvd_probe_kernel   read-only / write-only / copy streams, dispatched or persistent (calibration).
 //
 // Descriptors and work items are relative to the (layer 0, K) slab; the pull kernel adds the
 // slab offset of each side, so one list serves every layer and both K and V (the receiver
@@ -797,6 +798,27 @@ __global__ __launch_bounds__(256) void kvd_copy_kernel(u32x4 *__restrict__ dst,
 {
     const uint64_t u = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     if (u < units) stream_store(__builtin_nontemporal_load(src + u), dst + u);
+}
+
+// Probes of the memory system on plain buffers, with the pull kernel's access width and cache
+// policies: what a stream of reads, a stream of writes and a copy reach when every workgroup does
+// one access per lane and the hardware dispatcher hands the workgroups out in address order
+// (DISPATCHED), and when a fixed grid of resident workgroups strides over the buffer instead
+// (the persistent form).  READ / WRITE select the streams.
+template <bool READ, bool WRITE, bool DISPATCHED>
+__global__ __launch_bounds__(256) void kvd_probe_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+                                                        uint64_t units, u32x4 fill)
+{
+    const uint64_t stride = DISPATCHED ? units : (uint64_t)gridDim.x * 256;
+    u32x4 seen = fill;
+    for (uint64_t u = (uint64_t)blockIdx.x * 256 + threadIdx.x; u < units; u += stride) {
+        u32x4 v = fill;
+        if (READ) v = __builtin_nontemporal_load(src + u);
+        if (WRITE) stream_store(v, dst + u);
+        seen ^= v;
+    }
+    // keeps the loads of the read-only form alive: no buffer of N(0,1) values xors to this pattern
+    if (READ && !WRITE && seen.x == 0x7FA57FA5u && seen.y == 0x7FA57FA5u && seen.z == 0x12345678u) stream_store(seen, dst);
 }
 
 }  // namespace

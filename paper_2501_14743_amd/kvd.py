@@ -101,12 +101,13 @@ def lib() -> ctypes.CDLL:
     L.kvd_plan_get_descriptors.argtypes = [vp, vp, ctypes.POINTER(kvd_span_t), ctypes.POINTER(kvd_piece_t),
                                            u64, ctypes.POINTER(u64)]
     L.kvd_copy_plain.argtypes = [vp, vp, u64, vp]
+    L.kvd_stream_probe.argtypes = [vp, vp, u64, u32, vp]
     L.kvd_free.argtypes = [vp]
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
                  "kvd_pull_layers", "kvd_pull_noalloc", "kvd_complete", "kvd_pull_notify",
                  "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
-                 "kvd_plan_get_descriptors", "kvd_copy_plain"):
+                 "kvd_plan_get_descriptors", "kvd_copy_plain", "kvd_stream_probe"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -237,6 +238,13 @@ def kvd_plan_get_descriptors(plan: int, stream: int = 0) -> np.ndarray:
 
 def kvd_copy_plain(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(lib().kvd_copy_plain(dst_ptr, src_ptr, nbytes, stream))
+
+
+PROBE_MODES = {"copy": 0, "read": 1, "write": 2, "copy_persistent": 3, "read_persistent": 4, "write_persistent": 5}
+
+
+def kvd_stream_probe(dst_ptr: int, src_ptr: int, nbytes: int, mode, stream: int = 0) -> None:
+    _check(lib().kvd_stream_probe(dst_ptr, src_ptr, nbytes, PROBE_MODES.get(mode, mode), stream))
 
 
 def kvd_free(handle: Optional[int]) -> None:

@@ -755,6 +755,27 @@ def test_plain_copy():
         kvd.kvd_copy_plain(b.data_ptr(), a.data_ptr() + 1, 16)
 
 
+@pytest.mark.parametrize("mode", sorted(kvd.PROBE_MODES))
+def test_stream_probes_touch_what_they_say(mode):
+    n = 3 * 4096 * 257
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    keep = src.clone()
+    torch.cuda.synchronize()
+    kvd.kvd_stream_probe(dst.data_ptr(), src.data_ptr(), n, mode)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
+    if mode.startswith("copy"):
+        assert torch.equal(dst, src)
+    elif mode.startswith("read"):
+        assert int((dst != 7).sum()) == 0
+    else:
+        assert int((dst.view(torch.int16) != 0x3C00).sum()) == 0
+    for bad in ((dst.data_ptr(), src.data_ptr(), 4095), (0, src.data_ptr(), 4096), (dst.data_ptr() + 8, src.data_ptr(), 4096)):
+        with pytest.raises(kvd.KvdError):
+            kvd.kvd_stream_probe(*bad, mode)
+
+
 def _frag_request(gs, gd, tokens, seed):
     rng = np.random.default_rng(seed)
     return wl.Request(tokens,
