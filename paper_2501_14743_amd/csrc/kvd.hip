@@ -3,7 +3,6 @@
 // Validation, the plan object and its scratch memory, and the launches of the kernels in
 // kvd_kernels.h (structures, device code and their description).
 
-#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -140,9 +139,8 @@ struct kvd_plan {
     // KVD_PLAN_COMPLETE_PER_REQUEST: where each request starts in the descriptor and work-item
     // tables (device), and the two streams its pulls alternate on with their fork / join events
     uint32_t *req_desc_dev, *req_item_dev;
-    hipStream_t notify_stream[kNotifyStreams], notify_tell;  // the pulls take turns on the first; the words are written on the last
-    hipEvent_t notify_fork, notify_join[kNotifyStreams + 1];
-    std::vector<hipEvent_t> notify_done;                      // one per request: set when its pull kernel has finished
+    hipStream_t notify_stream[kNotifyStreams];
+    hipEvent_t notify_fork, notify_join[kNotifyStreams];
     bool notify_ready;
 };
 
@@ -241,11 +239,7 @@ void free_scratch(kvd_plan *p)
             (void)hipStreamSynchronize(p->notify_stream[i]);
             (void)hipStreamDestroy(p->notify_stream[i]);
         }
-        (void)hipStreamSynchronize(p->notify_tell);
-        (void)hipStreamDestroy(p->notify_tell);
-        for (int i = 0; i <= kNotifyStreams; ++i) (void)hipEventDestroy(p->notify_join[i]);
-        for (hipEvent_t e : p->notify_done) (void)hipEventDestroy(e);
-        p->notify_done.clear();
+        for (int i = 0; i < kNotifyStreams; ++i) (void)hipEventDestroy(p->notify_join[i]);
         (void)hipEventDestroy(p->notify_fork);
         p->notify_ready = false;
     }
@@ -417,22 +411,17 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     return KVD_OK;
 }
 
-// The side streams (default priority) of the per-request pulls, the events they fork from and join
-// at, and one event per request of the plan.
+// The side streams (default priority) that the per-request pulls take turns on, and the events they
+// fork from and join at.
 int ensure_notify_streams(kvd_plan *p)
 {
-    if (!p->notify_ready) {
-        KVD_HIP(hipEventCreateWithFlags(&p->notify_fork, hipEventDisableTiming));
-        for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamCreateWithFlags(&p->notify_stream[i], hipStreamNonBlocking));
-        KVD_HIP(hipStreamCreateWithFlags(&p->notify_tell, hipStreamNonBlocking));
-        for (int i = 0; i <= kNotifyStreams; ++i) KVD_HIP(hipEventCreateWithFlags(&p->notify_join[i], hipEventDisableTiming));
-        p->notify_ready = true;
+    if (p->notify_ready) return KVD_OK;
+    KVD_HIP(hipEventCreateWithFlags(&p->notify_fork, hipEventDisableTiming));
+    for (int i = 0; i < kNotifyStreams; ++i) {
+        KVD_HIP(hipStreamCreateWithFlags(&p->notify_stream[i], hipStreamNonBlocking));
+        KVD_HIP(hipEventCreateWithFlags(&p->notify_join[i], hipEventDisableTiming));
     }
-    while (p->notify_done.size() < p->reqs.size()) {
-        hipEvent_t e;
-        KVD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        p->notify_done.push_back(e);
-    }
+    p->notify_ready = true;
     return KVD_OK;
 }
 
@@ -911,15 +900,17 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
 
     // Request k's reads run as one launch; consecutive requests alternate between two side streams, so
     // the next request's reads are in flight while this one's last workgroups drain (section 4.2: reads
-    // of other requests do not wait for a completion).  Each launch carries an event that is set when
-    // that kernel has finished; a third stream waits for the events in request order and stores each
-    // request's word behind its own (completions are sent one after the other, as in the paper).
-    // The side streams start behind everything enqueued on `stream` so far, and `stream` continues
-    // behind all of them.
+    // of other requests do not wait for a completion).  Stream order makes a request's launch complete
+    // before the next launch on its side stream begins, and that launch's first workgroup stores the
+    // request's word.  The side streams start behind everything enqueued on `stream` so far, and
+    // `stream` continues behind both.
+    constexpr int T = 64;
+    for (const ReqHost &r : p->reqs)
+        if (((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8 >= (1ull << 31))
+            return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
     hipStream_t st = (hipStream_t)stream;
     KVD_HIP(hipEventRecord(p->notify_fork, st));
     for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamWaitEvent(p->notify_stream[i], p->notify_fork, 0));
-    constexpr int T = 64;
     const uint32_t n_req = (uint32_t)p->reqs.size();
     for (uint32_t k = 0; k < n_req; ++k) {
         const ReqHost &r = p->reqs[k];
@@ -940,7 +931,6 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
         a.announce = k >= (uint32_t)kNotifyStreams ? words_dev + (k - kNotifyStreams) : nullptr;
         a.announce_value = value;
         const uint64_t gx = ((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8;
-        if (gx >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
         hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, side, p->geo, a);
         KVD_HIP(hipGetLastError());
         if (k + kNotifyStreams >= n_req) {
@@ -948,8 +938,8 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
             KVD_HIP(hipGetLastError());
         }
     }
-    for (int i = 0; i <= kNotifyStreams; ++i) {
-        KVD_HIP(hipEventRecord(p->notify_join[i], i < kNotifyStreams ? p->notify_stream[i] : p->notify_tell));
+    for (int i = 0; i < kNotifyStreams; ++i) {
+        KVD_HIP(hipEventRecord(p->notify_join[i], p->notify_stream[i]));
         KVD_HIP(hipStreamWaitEvent(st, p->notify_join[i], 0));
     }
     return KVD_OK;

@@ -413,6 +413,33 @@ def test_per_request_completion_inside_one_batched_pull():
     x.close()
 
 
+def test_per_request_completion_recorded_into_a_hip_graph():
+    """kvd_pull_notify forks to its side streams and joins again, so a recording stream records all of it: three
+    replays with eager fills between them, each checked against the oracle and for its words."""
+    w = wl.config3(num_layers=2, num_requests=9, median=300.0, hi=2048)
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    x.build(batch=True)
+    words = torch.zeros(len(w.requests), dtype=torch.int64, device="cuda")
+    x.plan.pull_notify(words.data_ptr(), 5, x.stream.cuda_stream)  # eager first: the side streams exist before the recording
+    x.stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=x.stream):
+        x.plan.pull_notify(words.data_ptr(), 6, x.stream.cuda_stream)
+    for replay in range(3):
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        words.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert words.tolist() == [6] * len(w.requests), f"replay {replay}"
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"replay {replay}")
+    del graph
+    x.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed-layers", "block-major", "ragged-relayout"])
 def test_per_request_completion_other_plan_kinds(kind):
     """Requests built one call at a time with different layer ranges, block-major pools (layers folded, wide
