@@ -493,8 +493,8 @@ def main() -> int:
                 y.plan.pull(sh)
                 us = timed(lambda: y.plan.pull(sh), 10)
                 p_bytes = y.plan.stats(sh)["payload_bytes"]
-                groups = []  # best of three groups of ten steps: the HIP runtime stalls once, for tens of
-                for _ in range(3):  # milliseconds, after some five hundred launches of a process
+                groups = []  # best of three groups of ten steps (wall clock on a shared host)
+                for _ in range(3):
                     t_step = time.perf_counter()
                     for _ in range(10):
                         y.plan.reset()
