@@ -125,6 +125,22 @@ def test_released_and_foreign_handles_are_refused_without_being_read():
     expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull, d.handle)
 
 
+def test_pull_notify_and_probe_refusals_need_no_gpu():
+    g = geom()
+    s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
+    words = np.zeros(4, np.int64)
+    plain = kvd.Plan(s, d, 2, 8)
+    expect(kvd.KVD_ERR_MISMATCH, plain.pull_notify, words.ctypes.data, 1)       # plan without per-request completion
+    per_request = kvd.Plan(s, d, 2, 8, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    per_request.pull_notify(words.ctypes.data, 1)                               # empty plan: nothing to announce
+    expect(kvd.KVD_ERR_MISMATCH, kvd.Plan(s, d, 2, 8, kvd.KVD_PLAN_COMPLETE_PER_REQUEST | kvd.KVD_PLAN_PERSISTENT).pull_notify,
+           words.ctypes.data, 1)
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull_notify, 0x10, words.ctypes.data, 1)  # not a plan
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_stream_probe, FAKE_DST, FAKE_SRC, 4095, "copy")
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_stream_probe, FAKE_DST, FAKE_SRC, 4096, 6)
+    expect(kvd.KVD_ERR_INVALID, kvd.kvd_stream_probe, 0, FAKE_SRC, 4096, "read")
+
+
 def test_build_descriptors_validates_before_launching():
     g = geom()
     s, d = kvd.Pool(FAKE_SRC, g), kvd.Pool(FAKE_DST, g)
