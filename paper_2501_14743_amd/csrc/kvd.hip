@@ -45,26 +45,39 @@ constexpr uint32_t kPlanTag = 0x6b76504cu;
 // Every handle this library has given out and not yet released.  A pointer is looked up here
 // before it is dereferenced, so a stale, foreign or already released handle is refused instead of
 // being read.  Guarded by a mutex; a lookup costs some tens of nanoseconds per call.
-std::mutex g_handles_mutex;
-std::unordered_set<const void *> g_handles;
+// The list and its mutex are created at first use and never destroyed, so that a release
+// that arrives while the process is shutting down still finds them.
+struct HandleList {
+    std::mutex mutex;
+    std::unordered_set<const void *> live;
+};
+
+HandleList &handle_list()
+{
+    static HandleList *list = new HandleList;
+    return *list;
+}
 
 void register_handle(const void *h)
 {
-    std::lock_guard<std::mutex> lock(g_handles_mutex);
-    g_handles.insert(h);
+    HandleList &l = handle_list();
+    std::lock_guard<std::mutex> lock(l.mutex);
+    l.live.insert(h);
 }
 
 bool is_live_handle(const void *h)
 {
-    std::lock_guard<std::mutex> lock(g_handles_mutex);
-    return g_handles.count(h) != 0;
+    HandleList &l = handle_list();
+    std::lock_guard<std::mutex> lock(l.mutex);
+    return l.live.count(h) != 0;
 }
 
 // True if h was live; it no longer is afterwards.
 bool retire_handle(const void *h)
 {
-    std::lock_guard<std::mutex> lock(g_handles_mutex);
-    return g_handles.erase(h) != 0;
+    HandleList &l = handle_list();
+    std::lock_guard<std::mutex> lock(l.mutex);
+    return l.live.erase(h) != 0;
 }
 
 struct ReqHost {
