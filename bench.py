@@ -310,21 +310,21 @@ def main() -> int:
             words = torch.zeros(len(w.requests), dtype=torch.int64).pin_memory()
             y.plan.pull_notify(words.data_ptr(), 1, sh)
             torch.cuda.synchronize()
-            value = [1]
+            epoch = [1]
 
             def notify():
-                value[0] += 1
-                y.plan.pull_notify(words.data_ptr(), value[0], sh)
+                epoch[0] += 1
+                y.plan.pull_notify(words.data_ptr(), epoch[0], sh)
             extras["per_request_completion_pull_notify_us"] = timed(notify, 10)
             extras["per_request_completion_plain_pull_of_same_plan_us"] = timed(lambda: y.plan.pull(sh), 10)
             extras["per_request_completion_descriptors"] = y.plan.stats(sh)["num_descriptors"]
             torch.cuda.synchronize()
-            value[0] += 1
+            epoch[0] += 1
             t = time.perf_counter()
-            y.plan.pull_notify(words.data_ptr(), value[0], sh)
+            y.plan.pull_notify(words.data_ptr(), epoch[0], sh)
             seen = {}
             while len(seen) < len(w.requests) and time.perf_counter() - t < 10:
-                for k in np.nonzero(words.numpy() == value[0])[0]:
+                for k in np.nonzero(words.numpy() == epoch[0])[0]:
                     seen.setdefault(int(k), time.perf_counter() - t)
             torch.cuda.synchronize()
             extras["per_request_completion_first_word_us"] = min(seen.values()) * 1e6
@@ -709,6 +709,7 @@ def main() -> int:
     }
     if cpu is not None:
         out["cpu_baseline"] = cpu
+    assert isinstance(out["value"], float) and out["value"] > 0 and isinstance(out["ms_per_step"], float)
     print(json.dumps(out), flush=True)
     x.close()
     return 0
