@@ -331,6 +331,21 @@ def main() -> int:
             extras["per_request_completion_median_word_us"] = float(np.median(list(seen.values()))) * 1e6
             extras["per_request_completion_last_word_us"] = max(seen.values()) * 1e6
             y.close()
+        # the same request through the entry point that allocates nothing (tables in kernel arguments, scratch in the
+        # library's static device array): whole call, wall clock
+        if not batch and wl.blocks_for(w.requests[0].seq_len, min(w.src.block_tokens, w.dst.block_tokens)) <= kvd.KVD_NOALLOC_MAX_BLOCKS:
+            r0 = w.requests[0]
+            sd, dd = kvd.pool_desc(src.data_ptr(), w.src), kvd.pool_desc(dst.data_ptr(), w.dst)
+
+            def noalloc():
+                kvd.kvd_pull_noalloc(sd, dd, r0.src_table, r0.dst_table, r0.seq_len, w.layer_begin, w.layer_end, 0, sh)
+            noalloc()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(20):
+                noalloc()
+            torch.cuda.synchronize()
+            extras["noalloc_call_us"] = (time.perf_counter() - t) / 20 * 1e6
         # practical ceilings: one contiguous device-to-device copy of the payload
         n = min(payload, 1 << 30)
         a = torch.empty(n, dtype=torch.uint8, device="cuda")

@@ -236,6 +236,16 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *it
 // Frees whatever of the plan's scratch exists (pointers are null until allocated).
 void free_scratch(kvd_plan *p)
 {
+    // the side streams of per-request pulls first: what is still running on them uses the memory below
+    if (p->notify_ready) {
+        for (int i = 0; i < kNotifyStreams; ++i) {
+            (void)hipStreamSynchronize(p->notify_stream[i]);
+            (void)hipStreamDestroy(p->notify_stream[i]);
+        }
+        for (int i = 0; i < kNotifyStreams; ++i) (void)hipEventDestroy(p->notify_join[i]);
+        (void)hipEventDestroy(p->notify_fork);
+        p->notify_ready = false;
+    }
     if (p->done_host) (void)hipHostFree(p->done_host);
     if (p->tables_src) (void)hipHostFree(p->tables_src);
     if (p->tables_dst) (void)hipHostFree(p->tables_dst);
@@ -247,15 +257,6 @@ void free_scratch(kvd_plan *p)
     if (p->hdr_dev) (void)hipFree(p->hdr_dev);
     if (p->req_desc_dev) (void)hipFree(p->req_desc_dev);
     if (p->req_item_dev) (void)hipFree(p->req_item_dev);
-    if (p->notify_ready) {
-        for (int i = 0; i < kNotifyStreams; ++i) {
-            (void)hipStreamSynchronize(p->notify_stream[i]);
-            (void)hipStreamDestroy(p->notify_stream[i]);
-        }
-        for (int i = 0; i < kNotifyStreams; ++i) (void)hipEventDestroy(p->notify_join[i]);
-        (void)hipEventDestroy(p->notify_fork);
-        p->notify_ready = false;
-    }
     p->req_desc_dev = p->req_item_dev = nullptr;
     p->done_host = nullptr;
     p->tables_src = p->tables_dst = nullptr;
