@@ -66,7 +66,7 @@ def _oracle_worker(cfg_no: int, reps: int, barrier, out) -> None:
 
 def host_cores() -> int:
     """Cores this process may use: its affinity mask, capped by the thread count the environment
-    sets for the machine's CPU share (OMP_NUM_THREADS), at most 16."""
+    sets for this process's share of the host (OMP_NUM_THREADS), at most 16."""
     n = len(os.sched_getaffinity(0))
     try:
         n = min(n, int(os.environ.get("OMP_NUM_THREADS", n)))
@@ -158,7 +158,7 @@ def main() -> int:
                     help="also launch the plain copy kernel a few times (for counter calibration runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (both pools live in one MI355X's HBM); "
+        print("bench.py: this benchmark runs on ONE GPU only (both pools live in one MI355X's HBM); "
               "run with --gpus 1", file=sys.stderr)
         return 2
 
