@@ -264,6 +264,18 @@ def main() -> int:
     achieved = 2 * payload / (pull_ms.mean() * 1e-3) / 1e9
     log(f"step {ms_per_step * 1e3:.1f} us, pull kernel mean {pull_ms.mean() * 1e3:.1f} us "
         f"(min {pull_ms.min() * 1e3:.1f}), {achieved:.0f} GB/s = {achieved / PEAK_HBM_GBPS:.1%} of peak")
+    # what the bracket itself costs: two event records with nothing between them, behind a kernel like in a step
+    # (reported beside the kernel time, not subtracted from it)
+    empty = []
+    for _ in range(20):
+        x.plan.reset()
+        x.build(batch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        empty.append(e0.elapsed_time(e1) * 1e3)
+    event_pair_us = float(np.mean(empty))
 
     # the timed work produced the right bytes: oracle on the first and the last layer
     _checker()
@@ -712,6 +724,7 @@ def main() -> int:
                      "frac": achieved / PEAK_HBM_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "kvd_pull_kernel", "kernel_us_mean": float(pull_ms.mean() * 1e3),
                      "kernel_us_min": float(pull_ms.min() * 1e3), "launches_timed": int(pull_ms.size),
+                     "empty_event_pair_us": event_pair_us,
                      "algorithmic_bytes_per_launch": 2 * payload},
         "step_host_us": {"p50": float(np.percentile(host_us, 50)), "p99": float(np.percentile(host_us, 99)),
                          "max": float(host_us.max()), "max_at_step": int(host_us.argmax()),
