@@ -16,7 +16,8 @@
  *                  kvd_pull : every (merged or unmerged) range is issued at once, no waiting
  *                  in between.
  *   Complete()  -> the caller's stream order / event after kvd_pull, or kvd_complete: a word in
- *                  memory that names the finished request.
+ *                  memory that names the finished request; kvd_pull_notify gives every request
+ *                  of a batched plan its own word, stored when its own reads are done (section 4.2).
  *
  * Conventions
  *   - Every call returns KVD_OK (0) or a negative kvd_status_t; kvd_last_error() gives a
