@@ -130,6 +130,20 @@ def test_queue_example_merges_across_requests():
     assert m[1].tolist() == [3 * 8192, 9 * 8192, 8192]
 
 
+def test_merging_stops_at_a_completion_in_the_queue():
+    """Section 4.2 pops the reads "until the first completion" and merges among those.  The same two reads of the
+    queue example merge when both are queued before any completion, and stay two transactions when R1's completion
+    sits between them (each request's reads merged by themselves, the lists put one behind the other)."""
+    t = paper_tensor()
+    r1s, r1d = (int(x) for x in GOLD["queue_R1"].split())
+    r2s, r2d = (int(x) for x in GOLD["queue_R2_first"].split())
+    r1 = orc.request_transactions(t, t, 0, [r1s], [r1d], 16)
+    r2 = orc.request_transactions(t, t, 0, [r2s], [r2d], 16)
+    assert orc.coalesce(np.concatenate([r1, r2])).tolist() == [[0, 5 * 8192, 2 * 8192]]
+    stopped = np.concatenate([orc.coalesce(r1), orc.coalesce(r2)])
+    assert stopped.tolist() == [[0, 5 * 8192, 8192], [8192, 6 * 8192, 8192]]
+
+
 def test_merge_needs_both_sides_contiguous():
     # remote contiguous, local not -> no merge; and the other way round
     assert len(orc.coalesce([[0, 0, 100], [100, 300, 100]])) == 2
