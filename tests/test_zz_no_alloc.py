@@ -97,6 +97,38 @@ def test_noalloc_layer_sub_range_and_no_coalesce():
 
 
 @gpu
+@pytest.mark.parametrize("kind", ["runs", "short-scattered"])
+def test_noalloc_recorded_into_a_hip_graph(kind):
+    """The call allocates nothing and carries the tables by value, so a recording stream records all of it (the
+    table pieces, the build, the region ordering of short transactions, the pull): three replays with eager fills
+    between them, each checked against the oracle."""
+    w = wl.config2(num_layers=3, pool_blocks=1024, tokens=5000) if kind == "runs" else \
+        wl.config4(num_layers=40, pool_blocks=2560, tokens=32768)
+    src_host = wl.host_pool_values(w.src, w.dtype, w.seed)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    r = w.requests[0]
+    sd, dd = kvd.pool_desc(src.data_ptr(), w.src), kvd.pool_desc(dst.data_ptr(), w.dst)
+
+    def call():
+        kvd.kvd_pull_noalloc(sd, dd, r.src_table, r.dst_table, r.seq_len, w.layer_begin, w.layer_end, 0, stream.cuda_stream)
+    call()  # eager first: the device's copy of the scratch array is looked up outside the recording
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call()
+    for replay in range(3):
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, f"{kind}: replay {replay}")
+    del graph
+
+
+@gpu
 def test_noalloc_largest_table_and_refusals():
     """8192 blocks per side is taken (19 pieces of the tables); one more block, or more work items than
     the array holds, is refused with KVD_ERR_CAPACITY before anything is enqueued."""
