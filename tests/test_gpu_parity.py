@@ -1157,6 +1157,35 @@ def test_random_small_transfers(seed):
     G.assert_bytes_equal(dst.cpu().numpy(), want, f"random case {seed}")
     G.assert_bytes_equal(src.cpu().numpy(), src_host, f"random case {seed}: source changed")
     plan.close()
+    # the same requests, one call each, through the entry point that allocates nothing
+    carried = flags & (kvd.KVD_PLAN_NO_COALESCE | kvd.KVD_PLAN_WHOLE_BLOCKS)
+    dst2 = G.device_pool_from_host(wl.host_pool_sentinel(gd))
+    sd, dd = kvd.pool_desc(src.data_ptr(), gs), kvd.pool_desc(dst2.data_ptr(), gd)
+    torch.cuda.synchronize()
+    for r, (l0, l1) in zip(reqs, ranges):
+        kvd.kvd_pull_noalloc(sd, dd, r.src_table, r.dst_table, r.seq_len, l0, l1, carried)
+    torch.cuda.synchronize()
+    G.assert_bytes_equal(dst2.cpu().numpy(), want, f"random case {seed}: kvd_pull_noalloc")
+    # and as a plan that completes request by request (every other seed; not for the persistent form, nor for
+    # re-layout between block-major pools, which kvd_pull_notify refuses)
+    relayout_bm = gs.block_major and gd.block_major and gs.layout != gd.layout and gs.num_kv_heads > 1
+    if seed % 2 == 0 and not (flags & kvd.KVD_PLAN_PERSISTENT) and not relayout_bm:
+        dst3 = G.device_pool_from_host(wl.host_pool_sentinel(gd))
+        words = torch.zeros(len(reqs), dtype=torch.int64, device="cuda")
+        plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst3.data_ptr(), gd), len(reqs),
+                        sum(max(len(r.src_table), len(r.dst_table)) for r in reqs), flags | kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+        torch.cuda.synchronize()
+        if batch:
+            plan.build_descriptors_batch([r.src_table for r in reqs], [r.dst_table for r in reqs],
+                                         [r.seq_len for r in reqs], ranges[0][0], ranges[0][1])
+        else:
+            for r, (l0, l1) in zip(reqs, ranges):
+                plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, l0, l1)
+        plan.pull_notify(words.data_ptr(), seed + 1)
+        torch.cuda.synchronize()
+        assert words.tolist() == [seed + 1] * len(reqs)
+        G.assert_bytes_equal(dst3.cpu().numpy(), want, f"random case {seed}: kvd_pull_notify")
+        plan.close()
 
 
 # ------------------------------------------------------------------ full-size configurations
