@@ -1132,7 +1132,7 @@ def _random_case(seed):
     return gs, gd, reqs, ranges, flags, batch
 
 
-@pytest.mark.parametrize("seed", range(100))
+@pytest.mark.parametrize("seed", range(300))
 def test_random_small_transfers(seed):
     gs, gd, reqs, ranges, flags, batch = _random_case(seed)
     say(f"seed {seed}: {gs} -> {gd}, lens {[r.seq_len for r in reqs]}, layers {ranges}, flags {flags}, batch {batch}")
