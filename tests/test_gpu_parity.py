@@ -440,6 +440,46 @@ def test_per_request_completion_recorded_into_a_hip_graph():
     x.close()
 
 
+def test_per_request_completion_with_more_requests_than_one_build_launch_takes():
+    """701 short requests: two launches of the build kernel, whose per-request tables continue each other; after a
+    reset the same plan takes a smaller batch."""
+    g = wl.PoolGeometry(2, 4096, 16, 2, 64, 2, wl.BHTD)
+    rng = np.random.default_rng(13)
+    free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+    reqs = []
+    for _ in range(701):
+        t = int(rng.integers(1, 70))
+        n = wl.blocks_for(t, 16)
+        reqs.append(wl.Request(t, wl.fragmented_allocation(rng, free_s, n, 4), wl.fragmented_allocation(rng, free_d, n, 4)))
+    w = wl.Workload("many-notify", g, g, reqs, "bf16", 13)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    sh = x.stream.cuda_stream
+    x.build(batch=True)
+    s_t, d_t = tl.oracle_tensors(g, None)[0], tl.oracle_tensors(g, None)[0]
+    per_request = [orc.coalesce(orc.request_transactions(s_t, d_t, 0, r.src_table, r.dst_table, r.seq_len)) for r in reqs]
+    assert np.array_equal(x.plan.descriptors(sh), np.concatenate(per_request))
+    words = torch.zeros(701, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    x.plan.pull_notify(words.data_ptr(), 3, sh)
+    x.stream.synchronize()
+    assert int((words != 3).sum()) == 0
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "701 requests, per-request completion")
+    # the same plan again with the first 40 requests only
+    w2 = wl.Workload("fewer", g, g, reqs[:40], "bf16", 13)
+    dst.view(torch.int16).fill_(wl.SENTINEL16)
+    words.zero_()
+    x.after_torch()
+    x.plan.reset()
+    x.plan.build_descriptors_batch([r.src_table for r in reqs[:40]], [r.dst_table for r in reqs[:40]], [r.seq_len for r in reqs[:40]], 0, 2, sh)
+    x.plan.pull_notify(words.data_ptr(), 4, sh)
+    x.stream.synchronize()
+    assert words.tolist() == [4] * 40 + [0] * 661
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w2, src_host), "40 requests after a reset")
+    x.close()
+
+
 @pytest.mark.parametrize("kind", ["mixed-layers", "block-major", "ragged-relayout"])
 def test_per_request_completion_other_plan_kinds(kind):
     """Requests built one call at a time with different layer ranges, block-major pools (layers folded, wide
