@@ -1261,7 +1261,30 @@ def _check_full(w, sample_layers):
         G.compare_layer_with_oracle(w, src, dst, layer)
     assert checksum == [int(src.view(torch.int16)[i::9973][:4096].sum()) for i in range(3)]
     x.close()
-    del src, dst
+    # the other entry points at full size, against the pool just verified: the call that allocates nothing
+    # (single requests), a completion word per request (the batch)
+    verified = dst.clone()
+    dst.view(torch.int16).fill_(wl.SENTINEL16)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    if len(w.requests) == 1:
+        say(f"{w.name}: kvd_pull_noalloc")
+        r = w.requests[0]
+        kvd.kvd_pull_noalloc(kvd.pool_desc(src.data_ptr(), w.src), kvd.pool_desc(dst.data_ptr(), w.dst), r.src_table, r.dst_table,
+                             r.seq_len, w.layer_begin, w.layer_end, 0, stream.cuda_stream)
+        stream.synchronize()
+    else:
+        say(f"{w.name}: kvd_pull_notify")
+        y = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST, stream=stream)
+        y.build(batch=True)
+        words = torch.zeros(len(w.requests), dtype=torch.int64, device="cuda")
+        stream.wait_stream(torch.cuda.current_stream())
+        y.plan.pull_notify(words.data_ptr(), 11, stream.cuda_stream)
+        stream.synchronize()
+        assert words.tolist() == [11] * len(w.requests)
+        y.close()
+    assert torch.equal(dst, verified)
+    del src, dst, verified
     torch.cuda.empty_cache()
 
 
