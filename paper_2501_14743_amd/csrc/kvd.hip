@@ -187,8 +187,9 @@ int check_pool_desc(const kvd_pool_desc_t &d, uint64_t *extent_out)
     if ((uint64_t)d.block_tokens * d.num_kv_heads > (1u << 20))
         return fail(KVD_ERR_INVALID, "block_tokens*num_kv_heads above 2^20");
     if ((uint64_t)d.stride_block * e >= (1ull << 36)) return fail(KVD_ERR_RANGE, "stride_block of 64 GiB or more");
-    const uint64_t block_axis = ((uint64_t)(d.num_blocks - 1) * d.stride_block + tile) * e;
-    if (block_axis >= (1ull << 50))
+    // in 128 bits: 2^32 blocks times a stride of up to 2^36 bytes does not fit 64
+    const unsigned __int128 block_axis = ((unsigned __int128)(d.num_blocks - 1) * (uint64_t)d.stride_block + tile) * e;
+    if (block_axis >= ((unsigned __int128)1 << 50))
         return fail(KVD_ERR_RANGE, "block axis spans more than 2^50 bytes");
     // the layer, K/V and block axes must nest without overlap, in whatever order the strides put them
     struct Axis { uint64_t n, stride; } ax[3] = {{d.num_layers, (uint64_t)d.stride_layer},
@@ -558,19 +559,21 @@ int init_plan(kvd_plan *p, const kvd_pool_desc_t &s, uint64_t src_extent, const 
     g.div_tb_src = make_fastdiv(g.tb_src);
     g.div_tb_dst = make_fastdiv(g.tb_dst);
 
-    // upper bounds of what the plan can hold: read transactions and work items
-    const uint64_t pieces_max = (uint64_t)max_total_blocks * (tmax / tmin);
+    // upper bounds of what the plan can hold: read transactions and work items (in 128 bits: the
+    // products of caller-chosen capacities do not fit 64 for absurd arguments, which must be refused)
+    typedef unsigned __int128 u128;
+    const u128 pieces_max = (u128)max_total_blocks * (tmax / tmin);
+    u128 max_txns = pieces_max;
     if (g.mode == kSpanHeadMajor)
-        p->max_txns = (g.tb_src == g.tb_dst) ? pieces_max + (uint64_t)max_requests * hk_max
-                                             : pieces_max * hk_max;
-    else
-        p->max_txns = pieces_max;
-    const uint64_t units_max = pieces_max * tmin * hk_max * g.du;
+        max_txns = (g.tb_src == g.tb_dst) ? pieces_max + (u128)max_requests * hk_max : pieces_max * hk_max;
+    u128 max_items;
     if (g.mode >= kRelayoutHT2TH)
-        p->max_items = pieces_max * tmin * g.hk / g.rows_per_item + p->max_txns + 1;
+        max_items = pieces_max * tmin * g.hk / g.rows_per_item + max_txns + 1;
     else
-        p->max_items = units_max / kChunkUnits + p->max_txns + 1;
-    if (p->max_items >= (1ull << 31) || p->max_txns >= (1ull << 31)) return fail(KVD_ERR_CAPACITY, "plan capacity too large");
+        max_items = pieces_max * tmin * hk_max * g.du / kChunkUnits + max_txns + 1;
+    if (max_items >= ((u128)1 << 31) || max_txns >= ((u128)1 << 31)) return fail(KVD_ERR_CAPACITY, "plan capacity too large");
+    p->max_txns = (uint64_t)max_txns;
+    p->max_items = (uint64_t)max_items;
     // destination regions for kvd_order_kernel: 2 MiB, or wider if the slab's block axis would
     // need more buckets than the kernel keeps
     const uint64_t dst_span16 = ((uint64_t)(d.num_blocks - 1) * d.stride_block +

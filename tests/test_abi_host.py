@@ -69,6 +69,9 @@ def test_pool_create_rejects_bad_metadata():
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=1 << 30, head_dim=2048, num_kv_heads=64))  # 2^53 bytes
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, g, g.stride_layer, g.stride_kv, 1 << 35)       # 64 GiB between blocks
     expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, g, 1 << 44, g.stride_kv, g.stride_block)   # absurd stride
+    # a block axis whose size wraps around 64 bits must not slip under the limit: 2^29 + 1 blocks, 2^35 bytes apart
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=(1 << 29) + 1), 0, 0, 1 << 34)
+    expect(kvd.KVD_ERR_RANGE, kvd.Pool, FAKE_SRC, geom(num_blocks=(1 << 32) - 1), 1 << 43, 1 << 42, 1 << 34)
     p = kvd.Pool(FAKE_SRC, g)
     assert p.handle
     p.close()
@@ -87,6 +90,9 @@ def test_plan_create_rejects_mismatch_and_overlap():
     expect(kvd.KVD_ERR_MISMATCH, kvd.Plan, s, kvd.Pool(FAKE_DST, geom(block_tokens=32, num_blocks=32)), 1, 8,
            kvd.KVD_PLAN_WHOLE_BLOCKS)
     expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 0, 8)
+    expect(kvd.KVD_ERR_CAPACITY, kvd.Plan, s, d, 1, (1 << 32) - 1)                      # more blocks than any launch could take
+    expect(kvd.KVD_ERR_CAPACITY, kvd.Plan, kvd.Pool(FAKE_SRC, geom(num_kv_heads=1 << 10, block_tokens=1 << 10, head_dim=2048, num_blocks=2)),
+           kvd.Pool(FAKE_SRC + (1 << 44), geom(num_kv_heads=1 << 10, block_tokens=1, head_dim=2048, num_blocks=2)), (1 << 32) - 1, (1 << 32) - 1)
     expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 1, 0)
     # touching but not overlapping is fine
     kvd.Plan(s, kvd.Pool(FAKE_SRC + g.total_bytes, g), 1, 8).close()
