@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <exception>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -664,7 +665,12 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out)
     p->tag = kPoolTag;
     p->d = *desc;
     p->extent_bytes = extent;
-    register_handle(p);
+    try {
+        register_handle(p);
+    } catch (const std::exception &) {
+        delete p;
+        return fail(KVD_ERR_CAPACITY, "out of host memory");
+    }
     *out = p;
     return KVD_OK;
 }
@@ -683,10 +689,16 @@ int kvd_plan_create(const kvd_pool_t *src, const kvd_pool_t *dst, uint32_t max_r
         return rc;
     }
     p->tag = kPlanTag;
-    p->dst_used.assign(dst->d.num_blocks, 0);
-    p->reqs.reserve(max_requests);
+    try {  // no exception may cross this boundary: a pool or a capacity too large for the host is a refusal
+        p->dst_used.assign(dst->d.num_blocks, 0);
+        p->reqs.reserve(std::min<uint32_t>(max_requests, 4096));
+        register_handle(p);
+    } catch (const std::exception &) {
+        delete p;
+        return fail(KVD_ERR_CAPACITY, "out of host memory for a plan of %u requests over a pool of %u blocks", max_requests,
+                    dst->d.num_blocks);
+    }
     p->allocated = false;
-    register_handle(p);
     *out = p;
     return KVD_OK;
 }
@@ -800,6 +812,12 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
     }
 
     // 3. commit on the host, then one launch per kMaxBatch requests
+    try {  // room for this call's requests first, so that nothing below can throw half-way
+        p->reqs.reserve(p->reqs.size() + add_reqs);
+    } catch (const std::exception &) {
+        unmark_call(n_requests, 0);
+        return fail(KVD_ERR_CAPACITY, "out of host memory");
+    }
     const size_t first_new = p->reqs.size();
     const bool same_layers = first_new > 0 && p->reqs.back().layer_begin == layer_begin &&
                              p->reqs.back().layer_end == layer_end;
@@ -1197,8 +1215,14 @@ int kvd_plan_get_descriptors(kvd_plan_t *p, void *stream, kvd_span_t *spans, kvd
     Header h;
     KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
     if (h.n_desc > p->max_txns) return fail(KVD_ERR_HIP, "corrupt plan header");
-    std::vector<Desc> d(h.n_desc);
-    std::vector<uint32_t> hi(h.n_desc);
+    std::vector<Desc> d;
+    std::vector<uint32_t> hi;
+    try {
+        d.resize(h.n_desc);
+        hi.resize(h.n_desc);
+    } catch (const std::exception &) {
+        return fail(KVD_ERR_CAPACITY, "out of host memory for %u descriptors", h.n_desc);
+    }
     KVD_HIP(hipMemcpy(d.data(), p->desc_dev, (size_t)h.n_desc * sizeof(Desc), hipMemcpyDeviceToHost));
     if (p->geo.wide)  // written only for plans with 48-bit offsets
         KVD_HIP(hipMemcpy(hi.data(), p->desc_hi_dev, (size_t)h.n_desc * sizeof(uint32_t), hipMemcpyDeviceToHost));

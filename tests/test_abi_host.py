@@ -215,6 +215,72 @@ def test_valid_build_needs_a_gpu_and_says_so():
     expect(kvd.KVD_ERR_HIP, plan.build_descriptors, ok, ok, 128, 0, 2)
 
 
+def test_host_checks_survive_random_arguments():
+    """3000 calls with arguments drawn from edge values (zero, huge, misaligned, negative, inconsistent): every one
+    returns a documented status, with a message on failure, and nothing is dereferenced or launched (no GPU here;
+    on a GPU machine the few that pass every check run small transfers on fake... so only pointer-free checks are drawn
+    there).  A crash of the process is the failure this test is for."""
+    import torch
+    rng = np.random.default_rng(20250114)
+    edge32 = [0, 1, 2, 3, 15, 16, 17, 64, 255, 1024, 1025, 32767, 32768, 1 << 20, (1 << 31) - 1, 1 << 31, (1 << 32) - 1]
+    edge64 = [-1, 0, 1, 8, 16, 24, 4096, 1 << 20, 1 << 35, (1 << 36) - 16, 1 << 36, 1 << 43, 1 << 44, (1 << 62)]
+    codes = {kvd.KVD_OK, kvd.KVD_ERR_INVALID, kvd.KVD_ERR_RANGE, kvd.KVD_ERR_MISMATCH, kvd.KVD_ERR_ALIAS,
+             kvd.KVD_ERR_CAPACITY, kvd.KVD_ERR_HIP}
+
+    def pick(values):
+        return int(values[int(rng.integers(len(values)))])
+
+    def random_desc(base):
+        if rng.random() < 0.8:  # a sane pool, mostly with one field disturbed
+            g = geom()
+            f = [base, g.num_layers, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim, g.elem_bytes, 0,
+                 g.stride_layer, g.stride_kv, g.stride_block]
+            if rng.random() < 0.7:
+                k = int(rng.integers(len(f)))
+                f[k] = pick(edge64 if k in (0, 8, 9, 10) else edge32)
+        else:
+            f = [pick([0, 8, 16, base]), pick(edge32), pick(edge32), pick(edge32), pick(edge32), pick(edge32),
+                 pick([0, 1, 2, 3, 4, 8, 16]), pick([0, 1, 2, 7]), pick(edge64), pick(edge64), pick(edge64)]
+        f[7] = f[7] % (1 << 31)
+        return kvd.kvd_pool_desc_t(*f)
+
+    L = kvd.lib()
+    have_gpu = torch.cuda.is_available()
+    accepted = 0
+    for _ in range(3000):
+        sd, dd = random_desc(FAKE_SRC), random_desc(FAKE_DST)
+        ps, pd = ctypes.c_void_p(), ctypes.c_void_p()
+        rs = L.kvd_pool_create(ctypes.byref(sd), ctypes.byref(ps))
+        rd = L.kvd_pool_create(ctypes.byref(dd), ctypes.byref(pd))
+        for rc in (rs, rd):
+            assert rc in codes and (rc == kvd.KVD_OK or kvd.kvd_last_error())
+        n = int(rng.integers(0, 12))
+        st = np.asarray(rng.integers(-3, 80, size=n), np.int32)
+        dt = np.asarray(rng.integers(-3, 80, size=n), np.int32)
+        seq, l0, l1 = pick([0, 1, 15, 16, 17, 100, 1 << 30, (1 << 32) - 1]), pick([0, 1, 2, 5]), pick([0, 1, 2, 3, 1 << 20])
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        if not have_gpu:  # with a GPU a call that passes every check would move bytes between fake addresses
+            rc = L.kvd_pull_noalloc(ctypes.byref(sd), ctypes.byref(dd), st.ctypes.data_as(i32p), n, dt.ctypes.data_as(i32p), n,
+                                    seq, l0, l1, pick([0, 1, 4, 8, 2, 64]), None)
+            assert rc in codes and (rc == kvd.KVD_OK or kvd.kvd_last_error())
+        if rs == kvd.KVD_OK and rd == kvd.KVD_OK:
+            plan = ctypes.c_void_p()
+            rc = L.kvd_plan_create(ps, pd, pick([0, 1, 4, (1 << 32) - 1]), pick([0, 1, 16, 1 << 20, (1 << 32) - 1]),
+                                   pick([0, 1, 2, 4, 8, 16, 32, 63]), ctypes.byref(plan))
+            assert rc in codes and (rc == kvd.KVD_OK or kvd.kvd_last_error())
+            if rc == kvd.KVD_OK:
+                accepted += 1
+                if not have_gpu:
+                    rc = L.kvd_build_descriptors(plan, st.ctypes.data_as(i32p), n, dt.ctypes.data_as(i32p), n, seq, l0, l1, None)
+                    assert rc in codes and (rc == kvd.KVD_OK or kvd.kvd_last_error())
+                assert L.kvd_pull(plan, None) in codes
+                assert L.kvd_plan_reset(plan) in codes
+                L.kvd_free(plan)
+        L.kvd_free(ps)
+        L.kvd_free(pd)
+    assert accepted > 50, accepted  # the draw does reach the deeper checks
+
+
 C_PROGRAM = r"""
 #include <stdio.h>
 #include <string.h>
