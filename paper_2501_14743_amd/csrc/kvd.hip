@@ -947,6 +947,7 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
     KVD_HIP(hipEventRecord(p->notify_fork, st));
     for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamWaitEvent(p->notify_stream[i], p->notify_fork, 0));
     const uint32_t n_req = (uint32_t)p->reqs.size();
+    hipError_t launch = hipSuccess;
     for (uint32_t k = 0; k < n_req; ++k) {
         const ReqHost &r = p->reqs[k];
         hipStream_t side = p->notify_stream[k % kNotifyStreams];
@@ -967,16 +968,20 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
         a.announce_value = value;
         const uint64_t gx = ((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8;
         hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, side, p->geo, a);
-        KVD_HIP(hipGetLastError());
-        if (k + kNotifyStreams >= n_req) {
+        launch = hipGetLastError();
+        if (launch == hipSuccess && k + kNotifyStreams >= n_req) {
             hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, side, words_dev + k, value);
-            KVD_HIP(hipGetLastError());
+            launch = hipGetLastError();
         }
+        if (launch != hipSuccess) break;
     }
+    // also after a failed launch: whatever did reach the side streams stays ordered before `stream`
     for (int i = 0; i < kNotifyStreams; ++i) {
         KVD_HIP(hipEventRecord(p->notify_join[i], p->notify_stream[i]));
         KVD_HIP(hipStreamWaitEvent(st, p->notify_join[i], 0));
     }
+    if (launch != hipSuccess)
+        return fail(KVD_ERR_HIP, "launch of a per-request pull failed (some requests were not moved): %s", hipGetErrorString(launch));
     return KVD_OK;
 }
 

@@ -122,6 +122,9 @@ constexpr uint32_t kMaxBatch = 512;  // requests one launch of the build kernel 
 // Builds that add at most this many work items write them from the build kernel itself; larger
 // ones leave that to a second, wide launch (one workgroup would take about 1 us per thousand items).
 constexpr uint32_t kInlineItems = 8192;
+// A build that adds at most this many descriptors keeps them in LDS from the translation to the
+// expansion, so that the prefix scan and the work items do not wait for global memory again.
+constexpr uint32_t kBuildLdsDescs = 1024;
 
 // One request of a batch, as the build kernel sees it.
 struct ReqDev {
@@ -260,6 +263,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     __shared__ uint8_t s_brk[kBuildThreads];
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
     __shared__ ReqDev s_req[kMaxBatch];
+    __shared__ Desc s_desc[kBuildLdsDescs];             // descriptors [from, from + kBuildLdsDescs) as they are written
 
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     if (a.n_req > 1) {
@@ -276,6 +280,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
     uint64_t prev_s = 0, prev_d = 0, prev_w = 0;
     if (n0 > 0 && !never_merge && a.may_merge_prev) {
         const Desc p = a.desc[n0 - 1];
+        if (tid == 0) s_desc[0] = p;  // it is descriptor `from` below; the loop's first barrier publishes it
         const uint32_t hi = g.wide ? a.desc_hi[n0 - 1] : 0u;
         const uint64_t s0 = ((uint64_t)(hi & 0xFFFFu) << 32) | p.src16, d0 = ((uint64_t)(hi >> 16) << 32) | p.dst16;
         have_prev = true;
@@ -284,6 +289,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         prev_w = g.wide ? (((s0 >> 31) << 32) | (d0 >> 31)) : 0ull;
     }
     const bool had_open = have_prev;
+    const uint32_t from = had_open ? n0 - 1 : n0;  // first descriptor this build writes or extends
     uint32_t runs = n0;
 
     for (uint32_t tile = 0; tile < a.n_txn; tile += kBuildThreads) {
@@ -342,16 +348,25 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             // descriptor this transaction belongs to = (breaks up to and including it) - 1
             const uint32_t run = runs + wave_prefix + before + (brk ? 1u : 0u) - 1u;
             if (first_of_request) a.req_desc[a.req_base + req] = run;
+            const bool in_lds = run - from < kBuildLdsDescs;
             if (brk) {
                 a.desc[run].src16 = (uint32_t)t.s16;
                 a.desc[run].dst16 = (uint32_t)t.d16;
                 if (g.wide) a.desc_hi[run] = (uint32_t)(t.s16 >> 32) | ((uint32_t)(t.d16 >> 32) << 16);
                 if (relayout) a.desc[run].a = t.meta;
+                if (in_lds) {
+                    s_desc[run - from].src16 = (uint32_t)t.s16;
+                    s_desc[run - from].dst16 = (uint32_t)t.d16;
+                    if (relayout) s_desc[run - from].a = t.meta;
+                }
             }
             // the last member of a descriptor (so far) records where it ends; a later tile or
             // a later request that continues it overwrites this
             const bool closes = (tid == tile_last) || s_brk[tid + 1];
-            if (!relayout && closes) a.desc[run].a = (uint32_t)(t.s16 + t.len16);
+            if (!relayout && closes) {
+                a.desc[run].a = (uint32_t)(t.s16 + t.len16);
+                if (in_lds) s_desc[run - from].a = (uint32_t)(t.s16 + t.len16);
+            }
         }
         runs += total;
         prev_s = next_prev_s;
@@ -370,7 +385,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
 
     // work-item prefix over the descriptors that are new or were extended
     const uint32_t n1 = runs;
-    const uint32_t from = had_open ? n0 - 1 : n0;
+    const bool in_lds = n1 - from <= kBuildLdsDescs;  // s_desc holds every descriptor of this build
     uint32_t first_item = 0;
     if (from > 0) {
         Desc p = a.desc[from - 1];
@@ -381,7 +396,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         const uint32_t i = base + tid;
         const bool v = i < n1;
         Desc d = {0, 0, 0, 0};
-        if (v) d = a.desc[i];
+        if (v) d = in_lds ? s_desc[i - from] : a.desc[i];
         const uint32_t c = v ? desc_items(g, d) : 0u;
         uint32_t incl = c;  // inclusive scan inside the wave
 #pragma unroll
@@ -398,7 +413,10 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
             wave_prefix += (w < wave) ? x : 0u;
             total += x;
         }
-        if (v) a.desc[i].prefix = carry + wave_prefix + incl - c;
+        if (v) {
+            a.desc[i].prefix = carry + wave_prefix + incl - c;
+            if (in_lds) s_desc[i - from].prefix = carry + wave_prefix + incl - c;
+        }
         carry += total;
         __syncthreads();
     }
@@ -410,8 +428,34 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
 
     // expand descriptors [from, n1) into work items [first_item, n_items), a window of
     // descriptors at a time with their prefixes staged in LDS for the item -> descriptor search
+    if (a.expand_inline && in_lds) {
+        // Every lane writes `per` consecutive work items: one search over the prefixes in LDS for
+        // its first item, then it walks on from descriptor to descriptor (each has at least one item).
+        const uint32_t nd = n1 - from;
+        const uint32_t per = (n_items - first_item + kBuildThreads - 1) / kBuildThreads;
+        const uint32_t c0 = first_item + tid * per, c1 = min(n_items, c0 + per);
+        if (c0 < c1) {
+            uint32_t lo = 0, hi = nd;  // largest i with prefix[i] <= c0
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s_desc[mid].prefix <= c0) lo = mid; else hi = mid;
+            }
+            Desc d = s_desc[lo];
+            uint32_t next = (lo + 1 < nd) ? s_desc[lo + 1].prefix : n_items;
+            uint32_t dhi = g.wide ? a.desc_hi[from + lo] : 0u;
+            for (uint32_t c = c0; c < c1; ++c) {
+                while (c >= next) {
+                    ++lo;
+                    d = s_desc[lo];
+                    next = (lo + 1 < nd) ? s_desc[lo + 1].prefix : n_items;
+                    if (g.wide) dhi = a.desc_hi[from + lo];
+                }
+                a.items[c] = make_item(g, d, dhi, c - d.prefix, a.layers);
+            }
+        }
+    }
     constexpr uint32_t kWin = 2 * kBuildThreads;
-    for (uint32_t w0 = from; a.expand_inline && w0 < n1; w0 += kWin) {
+    for (uint32_t w0 = from; a.expand_inline && !in_lds && w0 < n1; w0 += kWin) {
         const uint32_t nw = min(kWin, n1 - w0);
         for (uint32_t i = tid; i < nw; i += kBuildThreads) s_buf[i] = a.desc[w0 + i].prefix;
         __syncthreads();
@@ -723,7 +767,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
 }
 
 // Persistent form, kept for comparison: a fixed grid of 1024-lane workgroups stages the coalesced
-// descriptors in LDS (a window of kLdsDescs at a time), every wave finds the descriptor of its
+// descriptors in LDS (a window of kBuildLdsDescs at a time), every wave finds the descriptor of its
 // 4 KiB work item by a search over the staged prefixes and moves it with four loads and four
 // stores per lane, for one slab after the other.  On MI355X this is 15-20 % of HBM peak slower
 // than kvd_pull_kernel: waves of a persistent grid drift apart and the store stream loses its order.

@@ -116,6 +116,40 @@ def test_batch_larger_than_one_launch_takes():
     x.close()
 
 
+@pytest.mark.parametrize("n_req,appended", [(250, False), (250, True), (500, False), (500, True)])
+def test_one_build_launch_below_and_above_its_descriptor_cache(n_req, appended):
+    """One build launch keeps up to 1024 new descriptors in LDS and falls back to global memory beyond that:
+    250 requests stay below (about 860 descriptors), 500 go above (about 1700).  `appended`: a request built
+    before the batch leaves a descriptor that the batch's first transaction continues."""
+    g = wl.PoolGeometry(2, 4096, 16, 2, 64, 2, wl.BTHD)
+    rng = np.random.default_rng(1000 + n_req)
+    free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+    free_s[:8] = free_d[:8] = False
+    first = wl.Request(64, np.arange(0, 4, dtype=np.int32), np.arange(0, 4, dtype=np.int32))
+    reqs = [first, wl.Request(40, np.arange(4, 7, dtype=np.int32), np.arange(4, 7, dtype=np.int32))]
+    for _ in range(n_req - 2):
+        t = int(rng.integers(33, 64))
+        n = wl.blocks_for(t, 16)
+        reqs.append(wl.Request(t, wl.fragmented_allocation(rng, free_s, n, 1), wl.fragmented_allocation(rng, free_d, n, 1)))
+    w = wl.Workload("cache", g, g, reqs, "bf16", 13)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
+    x = G.GpuTransfer(w, src, dst)
+    rest = reqs
+    if appended:
+        x.plan.build_descriptors(first.src_table, first.dst_table, first.seq_len, 0, 2, x.stream.cuda_stream)
+        rest = reqs[1:]
+    x.plan.build_descriptors_batch([r.src_table for r in rest], [r.dst_table for r in rest],
+                                   [r.seq_len for r in rest], 0, 2, x.stream.cuda_stream)
+    x.pull()
+    x.stream.synchronize()
+    want = tl.oracle_plan_descriptors(w, 0, 0)
+    assert (len(want) < 1024) == (n_req == 250), len(want)
+    assert np.array_equal(x.plan.descriptors(x.stream.cuda_stream), want)
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "descriptor cache")
+    x.close()
+
+
 def test_wide_expansion_continues_an_open_descriptor():
     """A long request (its work items are written by the separate wide launch) that continues the
     previous request's last descriptor, whose last work item was a short one; then another long
