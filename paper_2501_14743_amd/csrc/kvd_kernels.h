@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
         prev_w = g.wide ? (((s0 >> 31) << 32) | (d0 >> 31)) : 0ull;
     }
     const bool had_open = have_prev;
-    const uint32_t from = had_open ? n0 - 1 : n0;  // first descriptor this build writes or extends
+    const uint32_t from = had_open ? n0 - 1 : n0;  // first descriptor this launch writes or extends
     uint32_t runs = n0;
 
     for (uint32_t tile = 0; tile < a.n_txn; tile += kBuildThreads) {
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
 
     // work-item prefix over the descriptors that are new or were extended
     const uint32_t n1 = runs;
-    const bool in_lds = n1 - from <= kBuildLdsDescs;  // s_desc holds every descriptor of this build
+    const bool in_lds = n1 - from <= kBuildLdsDescs;  // s_desc holds every descriptor of this launch
     uint32_t first_item = 0;
     if (from > 0) {
         Desc p = a.desc[from - 1];

@@ -217,9 +217,10 @@ def test_valid_build_needs_a_gpu_and_says_so():
 
 def test_host_checks_survive_random_arguments():
     """3000 calls with arguments drawn from edge values (zero, huge, misaligned, negative, inconsistent): every one
-    returns a documented status, with a message on failure, and nothing is dereferenced or launched (no GPU here;
-    on a GPU machine the few that pass every check run small transfers on fake... so only pointer-free checks are drawn
-    there).  A crash of the process is the failure this test is for."""
+    returns a documented status, with a message on failure, and nothing is dereferenced or launched.  Without a GPU a
+    call that passes every check fails at its first HIP call; on a machine with one it would move bytes between the
+    fake pool addresses, so the calls that could get that far are left out there.  A crash of the process is the
+    failure this test is for."""
     import torch
     rng = np.random.default_rng(20250114)
     edge32 = [0, 1, 2, 3, 15, 16, 17, 64, 255, 1024, 1025, 32767, 32768, 1 << 20, (1 << 31) - 1, 1 << 31, (1 << 32) - 1]
