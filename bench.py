@@ -342,6 +342,19 @@ def main() -> int:
             extras["per_request_completion_first_word_us"] = min(seen.values()) * 1e6
             extras["per_request_completion_median_word_us"] = float(np.median(list(seen.values()))) * 1e6
             extras["per_request_completion_last_word_us"] = max(seen.values()) * 1e6
+            # neighbouring short requests announced together: a launch holds at least that many tokens
+            grouped = {}
+            for min_tokens in (512, 1024, 2048, 4096):
+                y.plan.set_completion_granularity(min_tokens)
+                notify()
+                torch.cuda.synchronize()
+                launches, tokens = 0, min_tokens
+                for r in w.requests:
+                    if tokens >= min_tokens:
+                        launches, tokens = launches + 1, 0
+                    tokens += r.seq_len
+                grouped[str(min_tokens)] = {"us": timed(notify, 10), "launches": launches}
+            extras["per_request_completion_grouped"] = grouped
             y.close()
         # the same request through the entry point that allocates nothing (tables in kernel arguments, scratch in the
         # library's static device array): whole call, wall clock

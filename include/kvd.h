@@ -257,7 +257,7 @@ int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, 
  * num_requests 8-byte words owned by the caller, in device memory or in pinned host memory that a CPU
  * thread polls; the caller chooses `value` so that it differs from what the words held before.
  * The plan must have been created with KVD_PLAN_COMPLETE_PER_REQUEST.  Requests are moved in queue order,
- * one launch each on two library-owned side streams in turn (default priority), so that the next request's
+ * one launch each (or per group, see kvd_plan_set_completion_granularity) on two library-owned side streams in turn (default priority), so that the next request's
  * reads are in flight while one request's last reads finish; `stream` is forked from and joined again:
  * work enqueued on `stream` after the call runs after the whole plan has been moved.  Work items are
  * walked in queue order (no grouping by destination region).  May be recorded into a HIP graph.
@@ -266,6 +266,19 @@ int kvd_pull_layers(kvd_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, 
  * block-major pools), KVD_ERR_HIP.
  */
 int kvd_pull_notify(kvd_plan_t *plan, uint64_t *words, uint64_t value, void *stream);
+
+/*
+ * How finely kvd_pull_notify announces (a plan created with KVD_PLAN_COMPLETE_PER_REQUEST; else
+ * KVD_ERR_MISMATCH).  0, the default: every request by itself, as soon as its own reads are done
+ * (section 4.2).  min_tokens > 0: consecutive requests of the queue that move the same layer range
+ * share a launch until it holds at least min_tokens tokens, and their words are stored together when
+ * the launch's reads are done - a request is then announced no earlier than its own reads and no later
+ * than those of the requests it shares the launch with.  A launch costs a few microseconds, so short
+ * requests are announced more cheaply in company (64 requests of 16..16384 tokens, 10.5 GiB: 6 to 8 %
+ * over kvd_pull one by one, 4.5 % with min_tokens = 1024, 3.9 % with 4096).  Takes effect at the next
+ * kvd_pull_notify; host only.
+ */
+int kvd_plan_set_completion_granularity(kvd_plan_t *plan, uint32_t min_tokens);
 
 /*
  * For callers that cannot allocate device memory - code under HIP graph capture, tight serving

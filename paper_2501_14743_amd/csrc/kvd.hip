@@ -156,6 +156,7 @@ struct kvd_plan {
     hipStream_t notify_stream[kNotifyStreams];
     hipEvent_t notify_fork, notify_join[kNotifyStreams];
     bool notify_ready;
+    uint32_t notify_min_tokens;  // kvd_pull_notify: a launch takes requests until it holds this many tokens (0: one each)
 };
 
 namespace {
@@ -378,9 +379,10 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     a.absolute_layers = whole ? 0u : 1u;
     a.layer0 = l0;
     a.req_item = nullptr;
-    a.req = a.n_req = 0;
+    a.req = a.req_end = a.n_req = 0;
     a.announce = nullptr;
     a.announce_value = 0;
+    a.announce_n = 0;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
         for (const ReqHost &r : p->reqs)
@@ -933,47 +935,72 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
     int rc = ensure_notify_streams(p);
     if (rc != KVD_OK) return rc;
 
-    // Request k's reads run as one launch; consecutive requests alternate between two side streams, so
-    // the next request's reads are in flight while this one's last workgroups drain (section 4.2: reads
-    // of other requests do not wait for a completion).  Stream order makes a request's launch complete
-    // before the next launch on its side stream begins, and that launch's first workgroup stores the
-    // request's word.  The side streams start behind everything enqueued on `stream` so far, and
-    // `stream` continues behind both.
+    // A group of requests' reads runs as one launch - one request per group unless the plan was given a
+    // completion granularity; consecutive groups alternate between two side streams, so the next
+    // group's reads are in flight while this one's last workgroups drain (section 4.2: reads of other
+    // requests do not wait for a completion).  Stream order makes a group's launch complete before the
+    // next launch on its side stream begins, and that launch's first workgroup stores the group's
+    // words.  The side streams start behind everything enqueued on `stream` so far, and `stream`
+    // continues behind both.
     constexpr int T = 64;
-    for (const ReqHost &r : p->reqs)
-        if (((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8 >= (1ull << 31))
+    const uint32_t n_req = (uint32_t)p->reqs.size();
+    struct Group { uint32_t begin, end; uint64_t item_bound; };
+    // where the group that starts at request k ends: requests are added while the group is below
+    // the granularity and the next request moves the same layers (a launch has one number of slabs)
+    auto group_at = [&](uint32_t k) {
+        Group g{k, k + 1, p->reqs[k].item_bound};
+        uint64_t tokens = p->reqs[k].seq_len;
+        while (g.end < n_req && tokens < p->notify_min_tokens && p->reqs[g.end].layer_begin == p->reqs[k].layer_begin &&
+               p->reqs[g.end].layer_end == p->reqs[k].layer_end) {
+            tokens += p->reqs[g.end].seq_len;
+            g.item_bound += p->reqs[g.end].item_bound;
+            ++g.end;
+        }
+        return g;
+    };
+    for (uint32_t k = 0; k < n_req; k = group_at(k).end)
+        if ((group_at(k).item_bound * (kChunkUnits / T) + 7) / 8 * 8 >= (1ull << 31))
             return fail(KVD_ERR_CAPACITY, "too many work items for one launch");
     hipStream_t st = (hipStream_t)stream;
     KVD_HIP(hipEventRecord(p->notify_fork, st));
     for (int i = 0; i < kNotifyStreams; ++i) KVD_HIP(hipStreamWaitEvent(p->notify_stream[i], p->notify_fork, 0));
-    const uint32_t n_req = (uint32_t)p->reqs.size();
     hipError_t launch = hipSuccess;
-    for (uint32_t k = 0; k < n_req; ++k) {
+    Group before[kNotifyStreams] = {};  // the group that ran last on each side stream (empty: none yet)
+    uint32_t turn = 0;
+    for (uint32_t k = 0; k < n_req && launch == hipSuccess; ++turn) {
+        const Group g = group_at(k);
         const ReqHost &r = p->reqs[k];
-        hipStream_t side = p->notify_stream[k % kNotifyStreams];
+        const int side_i = (int)(turn % kNotifyStreams);
+        hipStream_t side = p->notify_stream[side_i];
         PullArgs a;
         a.src_base = (const unsigned char *)p->src.base;
         a.dst_base = (unsigned char *)p->dst.base;
-        a.items = p->items_dev;  // queue order: a request's work items are one range of the table
+        a.items = p->items_dev;  // queue order: a group's work items are one range of the table
         a.hdr = p->hdr_dev;
         a.slabs = (p->fold_layers ? 1u : r.layer_end - r.layer_begin) << p->geo.kv_shift;
         a.absolute_layers = 0;
         a.layer0 = 0;
         a.req_item = p->req_item_dev;
-        a.req = k;
+        a.req = g.begin;
+        a.req_end = g.end;
         a.n_req = n_req;
-        // the word of the request that ran on this side stream before this one is stored by this
-        // launch's first workgroup; the last request of each side stream gets a launch for its word
-        a.announce = k >= (uint32_t)kNotifyStreams ? words_dev + (k - kNotifyStreams) : nullptr;
+        // the words of the group that ran on this side stream before this one are stored by this
+        // launch's first workgroup; the last group of each side stream gets a launch for its words
+        const Group &b = before[side_i];
+        a.announce = b.end > b.begin ? words_dev + b.begin : nullptr;
+        a.announce_n = b.end - b.begin;
         a.announce_value = value;
-        const uint64_t gx = ((uint64_t)r.item_bound * (kChunkUnits / T) + 7) / 8 * 8;
+        const uint64_t gx = (g.item_bound * (kChunkUnits / T) + 7) / 8 * 8;
         hipLaunchKernelGGL(kvd_pull_kernel<T>, dim3((uint32_t)gx, a.slabs), dim3(T), 0, side, p->geo, a);
         launch = hipGetLastError();
-        if (launch == hipSuccess && k + kNotifyStreams >= n_req) {
-            hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, side, words_dev + k, value);
-            launch = hipGetLastError();
-        }
-        if (launch != hipSuccess) break;
+        before[side_i] = g;
+        k = g.end;
+    }
+    for (int i = 0; i < kNotifyStreams && launch == hipSuccess; ++i) {
+        const Group &b = before[i];
+        if (b.end == b.begin) continue;
+        hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, p->notify_stream[i], words_dev + b.begin, b.end - b.begin, value);
+        launch = hipGetLastError();
     }
     // also after a failed launch: whatever did reach the side streams stays ordered before `stream`
     for (int i = 0; i < kNotifyStreams; ++i) {
@@ -982,6 +1009,15 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
     }
     if (launch != hipSuccess)
         return fail(KVD_ERR_HIP, "launch of a per-request pull failed (some requests were not moved): %s", hipGetErrorString(launch));
+    return KVD_OK;
+}
+
+int kvd_plan_set_completion_granularity(kvd_plan_t *p, uint32_t min_tokens)
+{
+    if (!as_plan(p)) return fail(KVD_ERR_INVALID, "not a plan handle");
+    if (!(p->flags & KVD_PLAN_COMPLETE_PER_REQUEST))
+        return fail(KVD_ERR_MISMATCH, "the plan was not created with KVD_PLAN_COMPLETE_PER_REQUEST");
+    p->notify_min_tokens = min_tokens;
     return KVD_OK;
 }
 
@@ -1099,7 +1135,7 @@ int kvd_complete(uint64_t *flag, uint64_t value, void *stream)
         return fail(KVD_ERR_INVALID, "flag is not memory the GPU can reach (device memory or pinned host memory)");
     }
     if (!at.devicePointer) return fail(KVD_ERR_INVALID, "flag is host memory that is not mapped into the device");
-    hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (uint64_t *)at.devicePointer, value);
+    hipLaunchKernelGGL(kvd_complete_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (uint64_t *)at.devicePointer, 1u, value);
     KVD_HIP(hipGetLastError());
     return KVD_OK;
 }
@@ -1124,9 +1160,10 @@ int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_
     a.absolute_layers = 0;
     a.layer0 = 0;
     a.req_item = nullptr;
-    a.req = a.n_req = 0;
+    a.req = a.req_end = a.n_req = 0;
     a.announce = nullptr;
     a.announce_value = 0;
+    a.announce_n = 0;
     const uint32_t cap = (uint32_t)std::min<uint64_t>(buffer_bytes / 4096, 1u << 20);
     for (uint32_t y = 0; y < a.slabs; ++y)
         for (uint32_t c0 = 0; c0 < h.n_items; c0 += cap) {

@@ -536,14 +536,16 @@ struct PullArgs {
     // 1: slab y is layer `layer0 + y / (K, V slabs)` of the pools, and items without it sit out
     uint32_t absolute_layers;
     uint32_t layer0;
-    // one request of the plan only (per-request completion): work items [req_item[req], req_item[req + 1])
-    // of the table, the last request's up to the table's end.  Null: the whole table.
+    // requests [req, req_end) of the plan only (per-request completion): work items
+    // [req_item[req], req_item[req_end]) of the table, up to the table's end if req_end = n_req.
+    // Null: the whole table.
     const uint32_t *req_item;
-    uint32_t req, n_req;
-    // A completion word to store before anything else (null: none): that of the request whose pull
-    // ran before this launch on the same stream, so that it costs no launch of its own.
+    uint32_t req, req_end, n_req;
+    // Completion words to store (null: none): those of the announce_n consecutive requests whose pull
+    // ran before this launch on the same stream, so that they cost no launch of their own.
     uint64_t *announce;
     uint64_t announce_value;
+    uint32_t announce_n;
 };
 
 // Streaming 16-byte store: non-temporal at device scope.  Measured on MI355X, this cache policy
@@ -640,7 +642,7 @@ __device__ __forceinline__ bool pick_piece(const Header h, const PullArgs &a, ui
     uint32_t lo = 0, hi = h.n_items;  // the part of the item table this launch moves
     if (a.req_item) {
         lo = a.req_item[a.req];
-        if (a.req + 1 < a.n_req) hi = a.req_item[a.req + 1];
+        if (a.req_end < a.n_req) hi = a.req_item[a.req_end];
     }
     const uint32_t pieces = (hi - lo) * kParts;
     if (h.n_items >= 4 * h.n_desc) {
@@ -674,8 +676,9 @@ __global__ __launch_bounds__(T) void kvd_pull_kernel(Geo g, PullArgs a)
     // end: the loads above stay scalar loads only while no atomic precedes them in program order
     // (with this store first, the header and item loads become vector loads and the whole kernel
     // runs a quarter slower, measured).
-    if (a.announce && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
-        __hip_atomic_store(a.announce, a.announce_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (a.announce && blockIdx.x == 0 && blockIdx.y == 0)
+        for (uint32_t i = threadIdx.x; i < a.announce_n; i += T)
+            __hip_atomic_store(a.announce + i, a.announce_value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Re-layout between pools that keep a block's layers together: the grid walks descriptor by
@@ -832,9 +835,11 @@ __global__ __launch_bounds__(1024) void kvd_pull_persistent_kernel(Geo g, PullAr
 // Complete() of section 4.1 as a message in memory: one word that says which request is done.
 // Stream order puts it behind the pulls; the release at system scope makes their writes visible
 // to whoever reads the word (another GPU, the host) before the word itself.
-__global__ void kvd_complete_kernel(uint64_t *flag, uint64_t value)
+__global__ void kvd_complete_kernel(uint64_t *flags, uint32_t n, uint64_t value)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (blockIdx.x == 0)
+        for (uint32_t i = threadIdx.x; i < n; i += blockDim.x)
+            __hip_atomic_store(flags + i, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 __global__ __launch_bounds__(256) void kvd_copy_kernel(u32x4 *__restrict__ dst,

@@ -94,6 +94,7 @@ def lib() -> ctypes.CDLL:
                                    u32, u32, u32, u32, vp]
     L.kvd_complete.argtypes = [vp, u64, vp]
     L.kvd_pull_notify.argtypes = [vp, vp, u64, vp]
+    L.kvd_plan_set_completion_granularity.argtypes = [vp, u32]
     L.kvd_pull_blockwise_memcpy.argtypes = [vp, vp]
     L.kvd_pull_staged.argtypes = [vp, vp, vp, u64, vp]
     L.kvd_plan_reset.argtypes = [vp]
@@ -106,6 +107,7 @@ def lib() -> ctypes.CDLL:
     L.kvd_free.restype = None
     for name in ("kvd_pool_create", "kvd_plan_create", "kvd_build_descriptors", "kvd_build_descriptors_batch", "kvd_pull",
                  "kvd_pull_layers", "kvd_pull_noalloc", "kvd_complete", "kvd_pull_notify",
+                 "kvd_plan_set_completion_granularity",
                  "kvd_pull_blockwise_memcpy", "kvd_pull_staged", "kvd_plan_reset", "kvd_plan_stats",
                  "kvd_plan_get_descriptors", "kvd_copy_plain", "kvd_stream_probe"):
         getattr(L, name).restype = ctypes.c_int
@@ -195,6 +197,10 @@ def kvd_pull_noalloc(src_desc: kvd_pool_desc_t, dst_desc: kvd_pool_desc_t, src_b
 
 def kvd_pull_notify(plan: int, words_ptr: int, value: int, stream: int = 0) -> None:
     _check(lib().kvd_pull_notify(plan, words_ptr, value, stream))
+
+
+def kvd_plan_set_completion_granularity(plan: int, min_tokens: int) -> None:
+    _check(lib().kvd_plan_set_completion_granularity(plan, min_tokens))
 
 
 def kvd_complete(flag_ptr: int, value: int, stream: int = 0) -> None:
@@ -294,6 +300,9 @@ class Plan:
 
     def pull_notify(self, words_ptr, value, stream=0):
         kvd_pull_notify(self.handle, words_ptr, value, stream)
+
+    def set_completion_granularity(self, min_tokens):
+        kvd_plan_set_completion_granularity(self.handle, min_tokens)
 
     def pull_layers(self, layer_begin, layer_end, stream=0):
         kvd_pull_layers(self.handle, layer_begin, layer_end, stream)

@@ -383,11 +383,13 @@ def _request_words(w, request, g):
     return mask
 
 
-def test_per_request_completion_inside_one_batched_pull():
+@pytest.mark.parametrize("min_tokens", [0, 1500, 1 << 30])
+def test_per_request_completion_inside_one_batched_pull(min_tokens):
     """kvd_pull_notify: every request of a batch gets its own completion word (section 4.2).  The descriptor
     list is the oracle's merge of each request's reads by itself (merging stops at a completion); a reader
     that waits for word k only, without synchronising any stream, finds request k's bytes equal to the
-    oracle's; at the end the whole pool equals the oracle's."""
+    oracle's; at the end the whole pool equals the oracle's.  min_tokens: requests announced one by one, in
+    launches of at least 1500 tokens, or all together (kvd_plan_set_completion_granularity)."""
     import time
     w = wl.config3(num_layers=4, num_requests=24, median=700.0, hi=4096)
     g = w.dst
@@ -395,6 +397,7 @@ def test_per_request_completion_inside_one_batched_pull():
     want = G.oracle_expected(w, src_host)
     src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
     x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    x.plan.set_completion_granularity(min_tokens)
     sh = x.stream.cuda_stream
     x.build(batch=True)
     got_desc = x.plan.descriptors(sh)
@@ -474,9 +477,11 @@ def test_per_request_completion_recorded_into_a_hip_graph():
     x.close()
 
 
-def test_per_request_completion_with_more_requests_than_one_build_launch_takes():
+@pytest.mark.parametrize("min_tokens", [0, 100, 3000])
+def test_per_request_completion_with_more_requests_than_one_build_launch_takes(min_tokens):
     """701 short requests: two launches of the build kernel, whose per-request tables continue each other; after a
-    reset the same plan takes a smaller batch."""
+    reset the same plan takes a smaller batch.  With min_tokens = 3000 a launch announces about 85 requests, more than
+    a wave has lanes."""
     g = wl.PoolGeometry(2, 4096, 16, 2, 64, 2, wl.BHTD)
     rng = np.random.default_rng(13)
     free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
@@ -489,6 +494,7 @@ def test_per_request_completion_with_more_requests_than_one_build_launch_takes()
     src_host = host_src(w)
     src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(g)
     x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    x.plan.set_completion_granularity(min_tokens)
     sh = x.stream.cuda_stream
     x.build(batch=True)
     s_t, d_t = tl.oracle_tensors(g, None)[0], tl.oracle_tensors(g, None)[0]
@@ -514,10 +520,12 @@ def test_per_request_completion_with_more_requests_than_one_build_launch_takes()
     x.close()
 
 
+@pytest.mark.parametrize("min_tokens", [0, 400])
 @pytest.mark.parametrize("kind", ["mixed-layers", "block-major", "ragged-relayout"])
-def test_per_request_completion_other_plan_kinds(kind):
+def test_per_request_completion_other_plan_kinds(kind, min_tokens):
     """Requests built one call at a time with different layer ranges, block-major pools (layers folded, wide
-    expansion) and a re-layout plan: device-memory words, whole pool against the oracle."""
+    expansion) and a re-layout plan: device-memory words, whole pool against the oracle.  With min_tokens = 400
+    neighbouring requests share a launch where they move the same layers."""
     rng = np.random.default_rng(17)
     if kind == "block-major":
         gs = gd = small_geom(block_major=True, num_blocks=256, num_layers=4)
@@ -536,6 +544,7 @@ def test_per_request_completion_other_plan_kinds(kind):
         tl.oracle_pull_workload(wl.Workload("one", gs, gd, [r], "bf16", 0, l0, l1), src_host, want)
     src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(gd)
     plan = kvd.Plan(kvd.Pool(src.data_ptr(), gs), kvd.Pool(dst.data_ptr(), gd), 5, 512, kvd.KVD_PLAN_COMPLETE_PER_REQUEST)
+    plan.set_completion_granularity(min_tokens)
     stream = torch.cuda.Stream()
     stream.wait_stream(torch.cuda.current_stream())
     for r, (l0, l1) in zip(reqs, ranges):
