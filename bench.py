@@ -147,6 +147,10 @@ def main() -> int:
     ap.add_argument("--size-sweep", action="store_true",
                     help="also time the pull of 1/8 ... 2x the configuration's token count (configurations 2 and 4), "
                          "the bandwidth-against-transfer-size curve of the paper's motivation")
+    ap.add_argument("--block-size-sweep", action="store_true",
+                    help="also time the pull of 1024 and 2048 lone blocks of 4 ... 128 KiB per (layer, K/V) (one KV head of "
+                         "128 bf16 values, 16 ... 512 tokens per block) in the configuration's pool memory: the "
+                         "bandwidth-against-block-size curve of the paper's motivation")
     ap.add_argument("--lone-blocks", action="store_true",
                     help="replace the configuration's block tables by tables in which every block is alone on both sides")
     ap.add_argument("--block-major", action="store_true",
@@ -547,6 +551,38 @@ def main() -> int:
                                       "step_us": step_us, "step_pct_of_peak": 2 * p_bytes / step_us / 1e3 / PEAK_HBM_GBPS * 100}
                 y.close()
             extras["size_sweep"] = sweep
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
+        # bandwidth against the block size (section 3 of the paper: 1024 / 2048 blocks of 4 KB and more): every block
+        # alone on both sides, one KV head per GPU as in a tensor-parallel share, the configuration's layer count
+        if args.block_size_sweep and not stats["relayout"]:
+            sweep = {}
+            pool_bytes = min(w.src.total_bytes, w.dst.total_bytes)
+            layers = w.src.num_layers
+            for block_tokens in (16, 32, 64, 128, 256, 512):
+                block_bytes = block_tokens * 128 * 2
+                pool_blocks = min(16384, pool_bytes // (2 * layers * block_bytes))
+                gb = wl.PoolGeometry(layers, pool_blocks, block_tokens, 1, 128, 2, wl.BHTD)
+                for n_blocks in (1024, 2048):
+                    if 2 * n_blocks > pool_blocks:
+                        continue
+                    rng = np.random.default_rng(w.seed + 4000 + block_tokens + n_blocks)
+                    wr = wl.Workload(f"lone-{block_bytes >> 10}KiB-x{n_blocks}", gb, gb,
+                                     [wl.Request(n_blocks * block_tokens, wl.scattered_table(rng, pool_blocks, n_blocks),
+                                                 wl.scattered_table(rng, pool_blocks, n_blocks))], "bf16", w.seed)
+                    y = G.GpuTransfer(wr, src, dst, stream=stream)
+                    y.build()
+                    y.plan.pull(sh)
+                    us = timed(lambda: y.plan.pull(sh), 10)
+                    st_y = y.plan.stats(sh)
+                    assert st_y["num_descriptors"] == n_blocks, st_y  # nothing merged: every block is alone
+                    p_bytes = st_y["payload_bytes"]
+                    sweep[f"{block_bytes >> 10}KiB_x{n_blocks}"] = {"payload_bytes": p_bytes, "pull_us": us,
+                                                                   "pct_of_peak": 2 * p_bytes / us / 1e3 / PEAK_HBM_GBPS * 100}
+                    y.close()
+            extras["block_size_sweep"] = sweep
             x.plan.reset()
             x.build(batch)
             x.plan.pull(sh)
