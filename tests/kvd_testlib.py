@@ -16,21 +16,40 @@ def oracle_tensors(g: wl.PoolGeometry, buffer: np.ndarray | None, first_layer: i
     window get no address and must not be used."""
     if num_layers is None:
         num_layers = g.num_layers - first_layer
+    stride_layer, stride_kv, stride_block = outer_strides(g)
     if g.layout == wl.BHTD:
         dims = [orc.KV, orc.B, orc.H, orc.L, orc.D]
         shape = [2, g.num_blocks, g.num_kv_heads, g.block_tokens, g.head_dim]
-        stride = [g.stride_kv, g.stride_block, g.block_tokens * g.head_dim, g.head_dim, 1]
+        stride = [stride_kv, stride_block, g.block_tokens * g.head_dim, g.head_dim, 1]
     else:
         dims = [orc.KV, orc.B, orc.L, orc.H, orc.D]
         shape = [2, g.num_blocks, g.block_tokens, g.num_kv_heads, g.head_dim]
-        stride = [g.stride_kv, g.stride_block, g.num_kv_heads * g.head_dim, g.head_dim, 1]
+        stride = [stride_kv, stride_block, g.num_kv_heads * g.head_dim, g.head_dim, 1]
     out = []
     for layer in range(g.num_layers):
         inside = first_layer <= layer < first_layer + num_layers
         out.append(orc.Tensor(buffer if inside else None,
-                              (layer - first_layer) * g.stride_layer * g.elem_bytes if inside else 0,
+                              (layer - first_layer) * stride_layer * g.elem_bytes if inside else 0,
                               dims, shape, stride, g.elem_bytes))
     return out
+
+
+def outer_strides(g: wl.PoolGeometry) -> tuple:
+    """(layer, K/V, block) strides in elements of the dense allocation the geometry names, worked out here
+    from the order of its axes - outermost first, each stride the product of the extents inside it - and not
+    taken from the geometry's own stride properties, which are what the library under test is given."""
+    extent = {"layer": g.num_layers, "kv": 2, "block": g.num_blocks}
+    if g.block_major:
+        order = ["block", "layer", "kv"]
+    elif g.kv_adjacent:
+        order = ["layer", "block", "kv"]
+    else:
+        order = ["layer", "kv", "block"]
+    stride, inside = {}, g.block_tokens * g.num_kv_heads * g.head_dim
+    for axis in reversed(order):
+        stride[axis] = inside
+        inside *= extent[axis]
+    return stride["layer"], stride["kv"], stride["block"]
 
 
 def oracle_pull_workload(w: wl.Workload, src_bytes: np.ndarray, dst_bytes: np.ndarray,
@@ -56,8 +75,8 @@ def oracle_plan_descriptors(w: wl.Workload, layer: int, kv: int) -> np.ndarray:
     merged = orc.coalesce(q)
     # the tensors carry no address here, so offsets are relative to the layer's tensor;
     # make them relative to the pool instead
-    merged[:, 0] += layer * w.src.stride_layer * w.src.elem_bytes
-    merged[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
+    merged[:, 0] += layer * outer_strides(w.src)[0] * w.src.elem_bytes
+    merged[:, 1] += layer * outer_strides(w.dst)[0] * w.dst.elem_bytes
     return merged
 
 
@@ -85,8 +104,8 @@ def oracle_plan_descriptors_block_major(w: wl.Workload) -> np.ndarray:
                 end = min(end, r.seq_len - big)
                 for layer in layers:
                     t = orc.request_transactions(s_all[layer], d_all[layer], -1, st, dt, end)
-                    t[:, 0] += layer * w.src.stride_layer * w.src.elem_bytes
-                    t[:, 1] += layer * w.dst.stride_layer * w.dst.elem_bytes
+                    t[:, 0] += layer * outer_strides(w.src)[0] * w.src.elem_bytes
+                    t[:, 1] += layer * outer_strides(w.dst)[0] * w.dst.elem_bytes
                     n = len(have[layer])
                     assert np.array_equal(t[:n], have[layer]) and len(t) > n
                     queue.append(t[n:])

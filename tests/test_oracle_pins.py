@@ -439,3 +439,13 @@ def test_oracle_equals_brute_force_on_random_tiny_geometries(seed):
         assert np.all(q[o, col][1:] >= (q[o, col] + q[o, 2])[:-1])  # no two ranges overlap
     m = orc.coalesce(q)
     assert m[:, 2].sum() == q[:, 2].sum() and len(m) <= len(q)
+
+
+@pytest.mark.parametrize("kw", [{}, {"kv_adjacent": True}, {"block_major": True}])
+def test_input_generator_strides_equal_the_test_glue_own_derivation(kw):
+    """The oracle is given strides that the test glue works out from the order of the pool's axes; the library is
+    given the strides the input generators carry.  Both describe the same dense allocation."""
+    for layout in (wl.BHTD, wl.BTHD):
+        g = wl.PoolGeometry(3, 7, 16, 2, 64, 2, layout, **kw)
+        assert tl.outer_strides(g) == (g.stride_layer, g.stride_kv, g.stride_block)
+        assert g.total_bytes == 3 * 2 * 7 * 16 * 2 * 64 * 2
