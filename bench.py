@@ -668,10 +668,34 @@ def main() -> int:
             td = wl.fixed_run_table(rng, w.dst.num_blocks, nblk, 1)
             o_d, o_s = np.argsort(td), np.argsort(ts)
             sweep["lone_blocks_queue_order"] = pull_pct(ts, td)
-            sweep["lone_blocks_grouped_by_2MiB_destination_region"] = pull_pct(ts, td, kvd.KVD_PLAN_NO_COALESCE)
+            sweep["lone_blocks_as_the_library_orders_them"] = pull_pct(ts, td, kvd.KVD_PLAN_NO_COALESCE)
             sweep["lone_blocks_queue_sorted_by_destination"] = pull_pct(ts[o_d], td[o_d])
             sweep["lone_blocks_queue_sorted_by_source"] = pull_pct(ts[o_s], td[o_s])
             sweep["lone_blocks_both_sides_in_address_order"] = pull_pct(np.sort(ts), np.sort(td))
+            # what the library's ordering is worth against the share of the pool the request takes: more lone blocks
+            # out of the same pool, in queue order and as the library orders them; pull alone, and the whole step
+            # (reset + build + ordering launches + pull)
+            for n in (nblk, 2 * nblk, 4 * nblk, 8 * nblk):
+                if 2 * n > min(w.src.num_blocks, w.dst.num_blocks):
+                    continue
+                rng = np.random.default_rng(w.seed + 5000 + n)
+                ts_n, td_n = wl.scattered_table(rng, w.src.num_blocks, n), wl.scattered_table(rng, w.dst.num_blocks, n)
+                for label, flags in (("queue_order", keep), ("as_the_library_orders_them", kvd.KVD_PLAN_NO_COALESCE)):
+                    wr = wl.Workload(f"{w.name}-density", w.src, w.dst, [wl.Request(n * w.src.block_tokens, ts_n, td_n)],
+                                     w.dtype, w.seed, w.layer_begin, w.layer_end)
+                    y = G.GpuTransfer(wr, src, dst, flags, stream=stream)
+                    y.build()
+                    y.plan.pull(sh)
+                    us = min(timed(lambda: y.plan.pull(sh), 10) for _ in range(2))
+
+                    def one_step():
+                        y.plan.reset()
+                        y.build()
+                        y.plan.pull(sh)
+                    step_us = min(timed(one_step, 10) for _ in range(2))
+                    y.close()
+                    sweep[f"{n}_lone_blocks_of_{w.src.num_blocks}_{label}"] = {
+                        "pull_us": us, "pct_of_peak": 2 * payload * n / nblk / us / 1e3 / PEAK_HBM_GBPS * 100, "step_us": step_us}
             # the configuration's own block ids: as queued, and paired / queued in address order
             r0 = w.requests[0]
             cs, cd = np.asarray(r0.src_table[:nblk]), np.asarray(r0.dst_table[:nblk])

@@ -90,8 +90,13 @@ typedef struct kvd_plan kvd_plan_t;
 #define KVD_PLAN_WHOLE_BLOCKS 4u /* move every slot of a request's last block, not only the tokens below
                                    seq_len: the block-granular transfer of section 4.1 (needs equal
                                    block sizes, else KVD_ERR_MISMATCH)                              */
-#define KVD_PLAN_QUEUE_ORDER 8u  /* never group the work items by destination region: kvd_pull walks them
-                                   in queue order whatever the plan looks like (ablation)           */
+#define KVD_PLAN_QUEUE_ORDER 8u  /* never put the work items in the order of their destination: kvd_pull walks
+                                   them in queue order whatever the plan looks like (ablation)      */
+#define KVD_PLAN_DESTINATION_ORDER 64u /* put the work items of short transactions in the order of their
+                                   destination (see kvd_pull) whatever the size of the transfer; by default
+                                   that is done only from 0.5 to 1 GiB of payload on, where one pull earns
+                                   the ordering launches back - a plan that is pulled many times (a recorded
+                                   graph) earns them back at any size                                 */
 #define KVD_PLAN_WIDE_OFFSETS 16u /* block-major plans: carry 48-bit offsets even where 32 bits reach the whole
                                    pool (the form pools above 64 GiB get by themselves); for testing  */
 #define KVD_PLAN_COMPLETE_PER_REQUEST 32u /* every request of the plan is followed by its own completion
@@ -221,9 +226,11 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
  * blocking; section 4.3: all layers in a single shot).  Every read is cut into work items of at
  * most 4 KiB and each (work item, layer, K/V) is moved by its own small workgroup, 16 bytes per
- * lane.  When the plan's transactions are short (fewer than four work items each, as for lone
- * 4 KiB blocks) the first pull after an append is preceded by one small launch that groups the work
- * items by destination region; re-layout plans between two pools whose blocks are the outermost
+ * lane.  When the plan's merged transactions are short (at most eight work items each on average,
+ * as for lone blocks of 4 to 32 KiB) the first pull after an append is preceded by one small launch
+ * that puts the work items in the order of their destination (by 2 MiB region below four items per
+ * transaction, whole transactions sorted by address from four to eight); which bytes are moved does
+ * not depend on it.  Re-layout plans between two pools whose blocks are the outermost
  * axis are walked block by block (all slabs of a block together) instead of slab by slab.  May be
  * called repeatedly; a plan with no requests is a no-op.
  * May be recorded into a HIP graph (it allocates nothing and waits for nothing); the graph then
@@ -286,12 +293,12 @@ int kvd_plan_set_completion_granularity(kvd_plan_t *plan, uint32_t min_tokens);
  * call that allocates nothing, on the device or through any allocating runtime routine.  The pools
  * are described by their metadata directly (no handles), the block tables are HOST arrays as for
  * kvd_build_descriptors (they travel in kernel arguments, 448 ids per side and launch), and what a
- * plan keeps in allocated scratch lives in one array of about 18.6 MiB that is part of the library's
+ * plan keeps in allocated scratch lives in one array of about 19.6 MiB that is part of the library's
  * code object and that every GPU the call is used on holds until the process ends.
  * Limits (KVD_ERR_CAPACITY, nothing is enqueued): at most KVD_NOALLOC_MAX_BLOCKS block-table
  * entries per side, 2^17 read transactions before merging and KVD_NOALLOC_MAX_WORK_ITEMS work items
  * of 4 KiB (per (layer, K/V); for block-major pools over all layers of the request).
- * `flags`: KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS, KVD_PLAN_QUEUE_ORDER or 0; anything else is
+ * `flags`: KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS, KVD_PLAN_QUEUE_ORDER, KVD_PLAN_DESTINATION_ORDER or 0; anything else is
  * KVD_ERR_INVALID.  Moves exactly the bytes that kvd_plan_create(flags) + kvd_build_descriptors +
  * kvd_pull move for the same arguments, with the same kernels, enqueued on `stream`; may be
  * recorded into a HIP graph (the tables are captured by value).  seq_len == 0 enqueues nothing.

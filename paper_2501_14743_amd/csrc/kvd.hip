@@ -128,6 +128,7 @@ struct kvd_plan {
     std::vector<ReqHost> reqs;
     std::vector<uint8_t> dst_used;  // one byte per destination block
     uint64_t used_src, used_dst, txns_total, item_bound, payload_bytes;
+    uint64_t desc_estimate;         // descriptors after merging as far as the host can tell from the tables (runs of blocks)
     uint32_t max_layers;            // largest layer count of any request in the plan
     // device / pinned scratch (allocated on first use)
     bool allocated;
@@ -139,7 +140,8 @@ struct kvd_plan {
     Desc *desc_dev;
     uint32_t *desc_hi_dev;  // upper halves of the descriptors' offsets (used only when geo.wide)
     Item *items_dev;
-    Item *ordered_dev;     // items grouped by destination region (plans of short descriptors)
+    Item *ordered_dev;     // items in the order of their destination (plans of short descriptors)
+    OrderEntry *order_dev; // per sorted descriptor: where its items go and come from (kvd_order_kernel -> kvd_order_copy_kernel)
     bool order_stale;      // requests were appended since ordered_dev was last written
     uint32_t order_shift;  // log2 of the region size in 16-byte units
     Header *hdr_dev;
@@ -236,6 +238,21 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *it
     }
 }
 
+// Pieces of memory a request consists of on both sides at once, as far as the adjacency of consecutive
+// entries in its two block tables tells: the descriptors it merges into (with KVD_PLAN_NO_COALESCE the
+// descriptors stay apart, but what matters for the order of the work is how the memory lies).  A hint
+// for launch decisions only: what is done with the work items is decided on the device from the build
+// kernel's own counts.
+uint64_t estimate_descriptors(const Geo &g, const int32_t *st, const int32_t *dt, uint32_t seq_len, uint32_t n_txn)
+{
+    if (g.mode >= kRelayoutHT2TH || g.tb_src != g.tb_dst) return n_txn;
+    const uint32_t blocks = ceil_div(seq_len, g.tb_src);
+    uint64_t runs = 1;
+    for (uint32_t i = 1; i < blocks; ++i) runs += (st[i] != st[i - 1] + 1 || dt[i] != dt[i - 1] + 1) ? 1u : 0u;
+    if (g.mode == kSpanHeadMajor && seq_len % g.tb_src) runs += g.hk - 1;  // a partial last block: one piece per head
+    return std::min<uint64_t>(runs, n_txn);
+}
+
 // Frees whatever of the plan's scratch exists (pointers are null until allocated).
 void free_scratch(kvd_plan *p)
 {
@@ -257,6 +274,7 @@ void free_scratch(kvd_plan *p)
     if (p->desc_hi_dev) (void)hipFree(p->desc_hi_dev);
     if (p->items_dev) (void)hipFree(p->items_dev);
     if (p->ordered_dev) (void)hipFree(p->ordered_dev);
+    if (p->order_dev) (void)hipFree(p->order_dev);
     if (p->hdr_dev) (void)hipFree(p->hdr_dev);
     if (p->req_desc_dev) (void)hipFree(p->req_desc_dev);
     if (p->req_item_dev) (void)hipFree(p->req_item_dev);
@@ -267,6 +285,7 @@ void free_scratch(kvd_plan *p)
     p->desc_dev = nullptr;
     p->desc_hi_dev = nullptr;
     p->items_dev = p->ordered_dev = nullptr;
+    p->order_dev = nullptr;
     p->hdr_dev = nullptr;
 }
 
@@ -287,6 +306,7 @@ int allocate_scratch(kvd_plan *p)
     KVD_HIP(hipMalloc((void **)&p->desc_hi_dev, (size_t)p->max_txns * sizeof(uint32_t)));
     KVD_HIP(hipMalloc((void **)&p->items_dev, (size_t)p->max_items * sizeof(Item)));
     KVD_HIP(hipMalloc((void **)&p->ordered_dev, (size_t)p->max_items * sizeof(Item)));
+    KVD_HIP(hipMalloc((void **)&p->order_dev, (size_t)p->max_txns * sizeof(OrderEntry)));
     KVD_HIP(hipMalloc((void **)&p->hdr_dev, sizeof(Header)));
     if (p->flags & KVD_PLAN_COMPLETE_PER_REQUEST) {
         KVD_HIP(hipMalloc((void **)&p->req_desc_dev, (size_t)p->max_requests * sizeof(uint32_t)));
@@ -403,18 +423,32 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
             KVD_HIP(hipGetLastError());
             return KVD_OK;
         }
-        // transactions shorter than four work items on average (known on the host before merging):
-        // the items may be scattered 4-16 KiB pieces, which move faster grouped by destination
-        // region; the extra launch (about 8 us) pays from roughly half a GiB of payload on
-        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->item_bound < 4 * p->txns_total &&
-            p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift) >= (1u << 17)) {
+        // descriptors of at most eight work items on average (estimated on the host from the runs in the
+        // block tables): scattered 4-32 KiB pieces, which move faster in the order of their destination.
+        // Below four items per descriptor the items are grouped by region (one launch of about 8 us, which
+        // pays from half a GiB of payload on); from four to eight whole descriptors are sorted (two
+        // launches, 20-55 us: level with the gain of one pull at a GiB, ahead beyond).  Re-layout plans gain
+        // nothing from the sort (measured).
+        const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
+        const bool group_items = p->item_bound < 4 * p->desc_estimate;
+        const bool sort_descriptors = !group_items && p->item_bound <= kSortItemsPerDesc * p->desc_estimate &&
+                                      p->geo.mode < kRelayoutHT2TH;
+        const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
+        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) &&
+            ((group_items && (always || pieces >= (1u << 17))) || (sort_descriptors && (always || pieces >= (1u << 18))))) {
             // recorded into a graph, the ordering runs at every replay and the plan still counts
             // as unordered for pulls outside the graph
             const bool capturing = is_capturing(stream);
             if (p->order_stale || capturing) {
-                hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream,
-                                   p->items_dev, p->ordered_dev, p->hdr_dev, p->order_shift, p->geo.wide);
+                hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, p->items_dev,
+                                   p->ordered_dev, p->hdr_dev, p->desc_dev, p->desc_hi_dev, p->order_dev, group_items ? 1u : 0u,
+                                   p->order_shift, p->geo.wide);
                 KVD_HIP(hipGetLastError());
+                if (!group_items) {
+                    hipLaunchKernelGGL(kvd_order_copy_kernel, dim3((uint32_t)(p->item_bound / 256 + 1)), dim3(256), 0,
+                                       (hipStream_t)stream, p->items_dev, p->ordered_dev, p->hdr_dev, p->order_dev);
+                    KVD_HIP(hipGetLastError());
+                }
                 if (!capturing) p->order_stale = false;
             }
             a.items = p->ordered_dev;
@@ -481,6 +515,11 @@ int init_plan(kvd_plan *p, const kvd_pool_desc_t &s, uint64_t src_extent, const 
               uint32_t max_requests, uint32_t max_total_blocks, uint32_t flags)
 {
     if (!max_requests || !max_total_blocks) return fail(KVD_ERR_INVALID, "zero capacity");
+    constexpr uint32_t kKnownFlags = KVD_PLAN_NO_COALESCE | KVD_PLAN_PERSISTENT | KVD_PLAN_WHOLE_BLOCKS | KVD_PLAN_QUEUE_ORDER |
+                                     KVD_PLAN_WIDE_OFFSETS | KVD_PLAN_COMPLETE_PER_REQUEST | KVD_PLAN_DESTINATION_ORDER;
+    if (flags & ~kKnownFlags) return fail(KVD_ERR_INVALID, "flags 0x%x: unknown bits", flags);
+    if ((flags & KVD_PLAN_QUEUE_ORDER) && (flags & KVD_PLAN_DESTINATION_ORDER))
+        return fail(KVD_ERR_INVALID, "KVD_PLAN_QUEUE_ORDER and KVD_PLAN_DESTINATION_ORDER exclude each other");
     if (s.num_kv_heads != d.num_kv_heads || s.head_dim != d.head_dim || s.elem_bytes != d.elem_bytes)
         return fail(KVD_ERR_MISMATCH, "pools differ in num_kv_heads, head_dim or elem_bytes");
     const uint32_t tmin = std::min(s.block_tokens, d.block_tokens);
@@ -605,8 +644,10 @@ constexpr size_t kNaOffDesc = kNaOffHeader + 256;
 constexpr size_t kNaOffDescHi = kNaOffDesc + (size_t)kNaMaxTxns * sizeof(Desc);
 constexpr size_t kNaOffItems = kNaOffDescHi + (size_t)kNaMaxTxns * sizeof(uint32_t);
 constexpr size_t kNaOffOrdered = kNaOffItems + (size_t)kNaMaxItems * sizeof(Item);
-constexpr size_t kNaScratchBytes = kNaOffOrdered + (size_t)kNaMaxItems * sizeof(Item);
-static_assert(kNaOffDesc % 256 == 0 && kNaOffDescHi % 256 == 0 && kNaOffItems % 256 == 0 && kNaOffOrdered % 256 == 0,
+constexpr size_t kNaOffOrder = kNaOffOrdered + (size_t)kNaMaxItems * sizeof(Item);
+constexpr size_t kNaScratchBytes = kNaOffOrder + (size_t)kNaMaxTxns * sizeof(OrderEntry);
+static_assert(kNaOffDesc % 256 == 0 && kNaOffDescHi % 256 == 0 && kNaOffItems % 256 == 0 && kNaOffOrdered % 256 == 0 &&
+                  kNaOffOrder % 256 == 0,
               "every part of the scratch array starts on a 256-byte boundary");
 static_assert(sizeof(Header) + sizeof(uint32_t) <= 128, "header and done word share the 256 bytes at kNaOffHeader");
 
@@ -714,7 +755,7 @@ int kvd_plan_reset(kvd_plan_t *p)
         for (uint32_t i = 0; i < r.n_dst; ++i)
             p->dst_used[(uint32_t)p->tables_dst[r.table_off_dst + i]] = 0;
     p->reqs.clear();
-    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = 0;
+    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = p->desc_estimate = 0;
     p->max_layers = 0;
     return KVD_OK;
 }
@@ -841,6 +882,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         p->used_src += r.n_src;
         p->used_dst += r.n_dst;
         p->payload_bytes += ((uint64_t)seq_len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
+        uint32_t n_txn = 0, items = 0;
+        request_sizes(g, seq_len, &n_txn, &items);
+        p->desc_estimate += estimate_descriptors(g, src_tbls[k], dst_tbls[k], seq_len, n_txn);
         p->reqs.push_back(r);
     }
     p->max_layers = std::max(p->max_layers, slab_layers);
@@ -1026,8 +1070,9 @@ int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, con
                      uint32_t layer_end, uint32_t flags, void *stream)
 {
     if (!src || !dst) return fail(KVD_ERR_INVALID, "null argument");
-    if (flags & ~(uint32_t)(KVD_PLAN_NO_COALESCE | KVD_PLAN_WHOLE_BLOCKS | KVD_PLAN_QUEUE_ORDER))
-        return fail(KVD_ERR_INVALID, "flags 0x%x: only KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS and KVD_PLAN_QUEUE_ORDER apply here", flags);
+    if (flags & ~(uint32_t)(KVD_PLAN_NO_COALESCE | KVD_PLAN_WHOLE_BLOCKS | KVD_PLAN_QUEUE_ORDER | KVD_PLAN_DESTINATION_ORDER))
+        return fail(KVD_ERR_INVALID, "flags 0x%x: only KVD_PLAN_NO_COALESCE, KVD_PLAN_WHOLE_BLOCKS, KVD_PLAN_QUEUE_ORDER and "
+                                     "KVD_PLAN_DESTINATION_ORDER apply here", flags);
     uint64_t src_extent = 0, dst_extent = 0;
     int rc = check_pool_desc(*src, &src_extent);
     if (rc != KVD_OK) return rc;
@@ -1093,9 +1138,11 @@ int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, con
     p->desc_hi_dev = (uint32_t *)(ptr + kNaOffDescHi);
     p->items_dev = (Item *)(ptr + kNaOffItems);
     p->ordered_dev = (Item *)(ptr + kNaOffOrdered);
+    p->order_dev = (OrderEntry *)(ptr + kNaOffOrder);
     // the host's bookkeeping of a plan that holds this one request
     p->txns_total = n_txn;
     p->item_bound = items;
+    p->desc_estimate = estimate_descriptors(g, src_tbl, dst_tbl, len, n_txn);
     p->payload_bytes = ((uint64_t)len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
     p->max_layers = slab_layers;
     p->order_stale = true;

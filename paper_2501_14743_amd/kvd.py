@@ -26,6 +26,7 @@ KVD_PLAN_NO_COALESCE = 1
 KVD_PLAN_PERSISTENT = 2
 KVD_PLAN_WHOLE_BLOCKS = 4
 KVD_PLAN_QUEUE_ORDER = 8
+KVD_PLAN_DESTINATION_ORDER = 64
 KVD_PLAN_WIDE_OFFSETS = 16
 KVD_PLAN_COMPLETE_PER_REQUEST = 32
 LAYOUTS = {"BHTD": KVD_LAYOUT_BHTD, "BTHD": KVD_LAYOUT_BTHD}

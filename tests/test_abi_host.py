@@ -142,6 +142,9 @@ def test_pull_notify_and_probe_refusals_need_no_gpu():
     expect(kvd.KVD_ERR_MISMATCH, kvd.Plan(s, d, 2, 8, kvd.KVD_PLAN_COMPLETE_PER_REQUEST | kvd.KVD_PLAN_PERSISTENT).pull_notify,
            words.ctypes.data, 1)
     expect(kvd.KVD_ERR_INVALID, kvd.kvd_pull_notify, 0x10, words.ctypes.data, 1)  # not a plan
+    expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 2, 8, 128)                       # unknown flag bit
+    expect(kvd.KVD_ERR_INVALID, kvd.Plan, s, d, 2, 8, kvd.KVD_PLAN_QUEUE_ORDER | kvd.KVD_PLAN_DESTINATION_ORDER)
+    kvd.Plan(s, d, 2, 8, kvd.KVD_PLAN_DESTINATION_ORDER).close()
     expect(kvd.KVD_ERR_MISMATCH, plain.set_completion_granularity, 1024)         # no completions to group
     per_request.set_completion_granularity(1024)
     per_request.set_completion_granularity(0)

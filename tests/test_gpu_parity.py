@@ -638,13 +638,109 @@ def test_region_ordering_of_short_scattered_transactions():
     x.close()
 
 
-@pytest.mark.parametrize("kind", ["runs", "short-scattered"])
+@pytest.mark.parametrize("case", ["lone-16KiB", "lone-16KiB-two-sort-chunks", "mixed-runs", "partial-heads",
+                                  "block-major-wide", "batch-per-request", "no-coalesce", "long-after-all"])
+def test_descriptor_sort_of_lone_medium_blocks(case):
+    """Descriptors of four to eight work items are sorted by destination address before the pull
+    (KVD_PLAN_DESTINATION_ORDER asks for it at any size): the bytes moved and the descriptor list stay the oracle's.
+    Covered: 16 and 32 KiB lone blocks, more descriptors than are sorted together (8192), lone blocks mixed with
+    short runs, a partial last block split per head, 48-bit offsets, several requests in one plan (the ordering is
+    left out by kvd_pull_notify and redone after an append), and the same through kvd_pull_noalloc."""
+    flags = kvd.KVD_PLAN_DESTINATION_ORDER
+    rng = np.random.default_rng(len(case))
+    if case == "lone-16KiB":
+        g = wl.PoolGeometry(2, 4096, 64, 1, 128, 2, wl.BHTD)            # 16 KiB per block and slab: 4 work items
+        reqs = [wl.Request(700 * 64 - 9, wl.scattered_table(rng, 4096, 700), wl.scattered_table(rng, 4096, 700))]
+    elif case == "lone-16KiB-two-sort-chunks":
+        g = wl.PoolGeometry(1, 9600, 64, 1, 128, 2, wl.BHTD)            # 9000 descriptors: more than are sorted together
+        reqs = [wl.Request(9000 * 64, wl.scattered_table(rng, 9600, 9000), wl.scattered_table(rng, 9600, 9000))]
+    elif case == "mixed-runs":
+        g = wl.PoolGeometry(2, 4096, 16, 4, 128, 2, wl.BHTD)            # 16 KiB blocks; runs of 1..3
+        free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+        reqs = [wl.Request(500 * 16, wl.fragmented_allocation(rng, free_s, 500, 3), wl.fragmented_allocation(rng, free_d, 500, 3))]
+    elif case == "partial-heads":
+        g = wl.PoolGeometry(2, 2048, 64, 4, 64, 2, wl.BHTD)             # 32 KiB blocks, tail of 5 tokens: 4 pieces of 640 B
+        reqs = [wl.Request(300 * 64 + 5, wl.scattered_table(rng, 2048, 301), wl.scattered_table(rng, 2048, 301))]
+    elif case == "block-major-wide":
+        g = wl.PoolGeometry(1, 3000, 16, 2, 128, 2, wl.BHTD, block_major=True)  # 16 KiB per block over K and V
+        flags |= kvd.KVD_PLAN_WIDE_OFFSETS
+        reqs = [wl.Request(1000 * 16, wl.scattered_table(rng, 3000, 1000), wl.scattered_table(rng, 3000, 1000))]
+    elif case == "batch-per-request":
+        g = wl.PoolGeometry(2, 4096, 64, 1, 128, 2, wl.BHTD)
+        flags |= kvd.KVD_PLAN_COMPLETE_PER_REQUEST
+        free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+        reqs = []
+        for n in (300, 1, 40, 500):
+            reqs.append(wl.Request(n * 64 - 1, wl.fragmented_allocation(rng, free_s, n, 1), wl.fragmented_allocation(rng, free_d, n, 1)))
+    elif case == "no-coalesce":
+        g = wl.PoolGeometry(2, 4096, 64, 1, 128, 2, wl.BHTD)            # lone 16 KiB blocks, nothing to merge either way
+        flags |= kvd.KVD_PLAN_NO_COALESCE
+        reqs = [wl.Request(600 * 64, wl.fixed_run_table(rng, 4096, 600, 1), wl.fixed_run_table(rng, 4096, 600, 1))]
+    else:
+        # blocks of 64 and 128 tokens: the host expects one descriptor per 16 KiB piece, but the tables are
+        # straight, everything merges, and the device keeps the queue order after all
+        g = wl.PoolGeometry(2, 1024, 64, 1, 128, 2, wl.BTHD)
+        gd = wl.PoolGeometry(2, 512, 128, 1, 128, 2, wl.BTHD)
+        reqs = [wl.Request(400 * 64, np.arange(100, 500, dtype=np.int32), np.arange(50, 250, dtype=np.int32))]
+    gd = gd if case == "long-after-all" else g
+    w = wl.Workload(case, g, gd, reqs, "bf16", 77)
+    src_host = host_src(w)
+    want = G.oracle_expected(w, src_host)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(gd)
+    x = G.GpuTransfer(w, src, dst, flags)
+    sh = x.stream.cuda_stream
+    # all but the last request, a pull, then the last one appended and two more pulls
+    for r in reqs[:-1]:
+        x.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, 0, g.num_layers, sh)
+    x.pull()
+    r = reqs[-1]
+    x.plan.build_descriptors(r.src_table, r.dst_table, r.seq_len, 0, g.num_layers, sh)
+    x.pull()
+    x.pull()
+    x.stream.synchronize()
+    G.assert_bytes_equal(dst.cpu().numpy(), want, case)
+    st = x.plan.stats(sh)
+    if case == "long-after-all":
+        assert st["num_descriptors"] == 1 and st["num_work_items"] == 1600, st
+    else:
+        assert 4 * st["num_descriptors"] <= st["num_work_items"] <= 8 * st["num_descriptors"], st  # the sorted form was taken
+    if case == "batch-per-request":
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        words = torch.zeros(len(reqs), dtype=torch.int64, device="cuda")
+        x.after_torch()
+        x.plan.pull_notify(words.data_ptr(), 5, sh)
+        x.stream.synchronize()
+        assert words.tolist() == [5] * len(reqs)
+        G.assert_bytes_equal(dst.cpu().numpy(), want, case + ", request by request")
+    elif not g.block_major:
+        s_t, d_t = tl.oracle_tensors(g, None)[0], tl.oracle_tensors(gd, None)[0]
+        q = np.concatenate([orc.request_transactions(s_t, d_t, 0, r.src_table, r.dst_table, r.seq_len) for r in reqs])
+        assert np.array_equal(x.plan.descriptors(sh), q if case == "no-coalesce" else orc.coalesce(q))  # still in queue order
+    x.close()
+    if len(reqs) == 1 and not (flags & kvd.KVD_PLAN_WIDE_OFFSETS) and len(reqs[0].src_table) <= kvd.KVD_NOALLOC_MAX_BLOCKS:
+        dst.view(torch.int16).fill_(wl.SENTINEL16)
+        torch.cuda.synchronize()
+        kvd.kvd_pull_noalloc(kvd.pool_desc(src.data_ptr(), g), kvd.pool_desc(dst.data_ptr(), gd), reqs[0].src_table, reqs[0].dst_table,
+                             reqs[0].seq_len, 0, g.num_layers, flags, 0)
+        torch.cuda.synchronize()
+        G.assert_bytes_equal(dst.cpu().numpy(), want, case + " through kvd_pull_noalloc")
+
+
+@pytest.mark.parametrize("kind", ["runs", "short-scattered", "medium-scattered"])
 def test_pull_recorded_into_a_hip_graph(kind):
     """kvd_pull inside a HIP graph: every replay moves the plan's bytes, also for plans whose work
-    items are grouped by region first; an eager pull between recording and the first replay is
-    right as well; builds refuse to be recorded."""
+    items are grouped by region or whose descriptors are sorted by destination first (those launches
+    are then part of the graph); an eager pull between recording and the first replay is right as
+    well; builds refuse to be recorded."""
+    flags = 0
     if kind == "runs":
         w = wl.config2(num_layers=2, pool_blocks=2048, tokens=5000)
+    elif kind == "medium-scattered":
+        g = wl.PoolGeometry(2, 4096, 64, 1, 128, 2, wl.BHTD)  # lone 16 KiB blocks
+        rng = np.random.default_rng(44)
+        flags = kvd.KVD_PLAN_DESTINATION_ORDER
+        w = wl.Workload("graph-medium", g, g, [wl.Request(900 * 64 - 7, wl.scattered_table(rng, 4096, 900),
+                                                          wl.scattered_table(rng, 4096, 900))], "bf16", 44)
     else:
         g = wl.PoolGeometry(16, 65536, 16, 1, 8, 2, wl.BHTD)
         rng = np.random.default_rng(43)
@@ -653,7 +749,7 @@ def test_pull_recorded_into_a_hip_graph(kind):
     src_host = host_src(w)
     want = G.oracle_expected(w, src_host)
     src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
-    x = G.GpuTransfer(w, src, dst)
+    x = G.GpuTransfer(w, src, dst, flags)
     x.build()
     x.stream.synchronize()
     graph = torch.cuda.CUDAGraph()
