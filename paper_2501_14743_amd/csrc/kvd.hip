@@ -129,6 +129,7 @@ struct kvd_plan {
     std::vector<uint8_t> dst_used;  // one byte per destination block
     uint64_t used_src, used_dst, txns_total, item_bound, payload_bytes;
     uint64_t desc_estimate;         // descriptors after merging as far as the host can tell from the tables (runs of blocks)
+    uint64_t dst_descents;          // how often the queue steps back in the destination pool (0: it is in destination order)
     uint32_t max_layers;            // largest layer count of any request in the plan
     // device / pinned scratch (allocated on first use)
     bool allocated;
@@ -243,8 +244,12 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *it
 // descriptors stay apart, but what matters for the order of the work is how the memory lies).  A hint
 // for launch decisions only: what is done with the work items is decided on the device from the build
 // kernel's own counts.
-uint64_t estimate_descriptors(const Geo &g, const int32_t *st, const int32_t *dt, uint32_t seq_len, uint32_t n_txn)
+uint64_t estimate_descriptors(const Geo &g, const int32_t *st, const int32_t *dt, uint32_t seq_len, uint32_t n_txn,
+                              uint64_t *dst_descents)
 {
+    // how often the destination table steps back: none at all means the queue is in destination order already
+    const uint32_t dst_blocks = ceil_div(seq_len, g.tb_dst);
+    for (uint32_t i = 1; i < dst_blocks; ++i) *dst_descents += dt[i] < dt[i - 1] ? 1u : 0u;
     if (g.mode >= kRelayoutHT2TH || g.tb_src != g.tb_dst) return n_txn;
     const uint32_t blocks = ceil_div(seq_len, g.tb_src);
     uint64_t runs = 1;
@@ -428,13 +433,14 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
         // Below four items per descriptor the items are grouped by region (one launch of about 8 us, which
         // pays from half a GiB of payload on); from four to eight whole descriptors are sorted (two
         // launches, 20-55 us: level with the gain of one pull at a GiB, ahead beyond).  Re-layout plans gain
-        // nothing from the sort (measured).
+        // nothing from the sort (measured), and a queue that never steps back in the destination pool is in that
+        // order already.
         const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
         const bool group_items = p->item_bound < 4 * p->desc_estimate;
         const bool sort_descriptors = !group_items && p->item_bound <= kSortItemsPerDesc * p->desc_estimate &&
                                       p->geo.mode < kRelayoutHT2TH;
         const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
-        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) &&
+        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->dst_descents > 0 &&
             ((group_items && (always || pieces >= (1u << 17))) || (sort_descriptors && (always || pieces >= (1u << 18))))) {
             // recorded into a graph, the ordering runs at every replay and the plan still counts
             // as unordered for pulls outside the graph
@@ -755,7 +761,7 @@ int kvd_plan_reset(kvd_plan_t *p)
         for (uint32_t i = 0; i < r.n_dst; ++i)
             p->dst_used[(uint32_t)p->tables_dst[r.table_off_dst + i]] = 0;
     p->reqs.clear();
-    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = p->desc_estimate = 0;
+    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = p->desc_estimate = p->dst_descents = 0;
     p->max_layers = 0;
     return KVD_OK;
 }
@@ -884,7 +890,8 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         p->payload_bytes += ((uint64_t)seq_len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
         uint32_t n_txn = 0, items = 0;
         request_sizes(g, seq_len, &n_txn, &items);
-        p->desc_estimate += estimate_descriptors(g, src_tbls[k], dst_tbls[k], seq_len, n_txn);
+        if (!p->reqs.empty() && dst_tbls[k][0] < p->tables_dst[p->reqs.back().table_off_dst + p->reqs.back().n_dst - 1]) ++p->dst_descents;
+        p->desc_estimate += estimate_descriptors(g, src_tbls[k], dst_tbls[k], seq_len, n_txn, &p->dst_descents);
         p->reqs.push_back(r);
     }
     p->max_layers = std::max(p->max_layers, slab_layers);
@@ -1142,7 +1149,7 @@ int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, con
     // the host's bookkeeping of a plan that holds this one request
     p->txns_total = n_txn;
     p->item_bound = items;
-    p->desc_estimate = estimate_descriptors(g, src_tbl, dst_tbl, len, n_txn);
+    p->desc_estimate = estimate_descriptors(g, src_tbl, dst_tbl, len, n_txn, &p->dst_descents);
     p->payload_bytes = ((uint64_t)len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
     p->max_layers = slab_layers;
     p->order_stale = true;

@@ -677,11 +677,12 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
         flags |= kvd.KVD_PLAN_NO_COALESCE
         reqs = [wl.Request(600 * 64, wl.fixed_run_table(rng, 4096, 600, 1), wl.fixed_run_table(rng, 4096, 600, 1))]
     else:
-        # blocks of 64 and 128 tokens: the host expects one descriptor per 16 KiB piece, but the tables are
-        # straight, everything merges, and the device keeps the queue order after all
+        # blocks of 64 and 128 tokens: the host expects one descriptor per 16 KiB piece, but the tables are two
+        # straight stretches, everything merges into two descriptors, and the device keeps the queue order after all
         g = wl.PoolGeometry(2, 1024, 64, 1, 128, 2, wl.BTHD)
         gd = wl.PoolGeometry(2, 512, 128, 1, 128, 2, wl.BTHD)
-        reqs = [wl.Request(400 * 64, np.arange(100, 500, dtype=np.int32), np.arange(50, 250, dtype=np.int32))]
+        reqs = [wl.Request(400 * 64, np.arange(100, 500, dtype=np.int32),
+                           np.concatenate([np.arange(150, 250), np.arange(50, 150)]).astype(np.int32))]
     gd = gd if case == "long-after-all" else g
     w = wl.Workload(case, g, gd, reqs, "bf16", 77)
     src_host = host_src(w)
@@ -701,7 +702,7 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
     G.assert_bytes_equal(dst.cpu().numpy(), want, case)
     st = x.plan.stats(sh)
     if case == "long-after-all":
-        assert st["num_descriptors"] == 1 and st["num_work_items"] == 1600, st
+        assert st["num_descriptors"] == 2 and st["num_work_items"] == 1600, st
     else:
         assert 4 * st["num_descriptors"] <= st["num_work_items"] <= 8 * st["num_descriptors"], st  # the sorted form was taken
     if case == "batch-per-request":
