@@ -137,7 +137,13 @@ typedef struct {
     uint64_t num_descriptors;  /* after coalescing, per (layer, kv)                              */
     uint64_t num_work_items;   /* 4 KiB pieces the descriptors expand to, per (layer, kv)        */
     uint64_t payload_bytes;    /* bytes one kvd_pull writes = bytes it reads                     */
+    uint32_t work_order;       /* how kvd_pull walks the work items: KVD_ORDER_*                 */
+    uint32_t reserved;
 } kvd_stats_t;
+
+#define KVD_ORDER_QUEUE 0u   /* as queued                                                           */
+#define KVD_ORDER_REGIONS 1u /* grouped by 2 MiB region of the destination (transactions below four work items) */
+#define KVD_ORDER_SORTED 2u  /* whole transactions sorted by destination address (four to eight work items)     */
 
 /*
  * Register one pool's tensor metadata (section 4.1, what Connect() exchanges; the pool's

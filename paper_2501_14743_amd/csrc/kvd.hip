@@ -392,6 +392,24 @@ const kvd_pool *as_pool(const void *h)
     return p->tag == kPoolTag ? p : nullptr;
 }
 
+// How kvd_pull walks the plan's work items, as the host decides it from the block tables.  Descriptors
+// of at most eight work items on average (estimated from the runs in the tables) are scattered 4-32 KiB
+// pieces, which move faster in the order of their destination.  Below four items per descriptor the
+// items are grouped by region (one launch of about 8 us, which pays from half a GiB of payload on);
+// from four to eight whole descriptors are sorted (two launches, 20-55 us: level with the gain of one
+// pull at a GiB, ahead beyond).  Re-layout plans gain nothing from the sort (measured), and a queue that
+// never steps back in the destination pool is in that order already.
+uint32_t work_order(const kvd_plan *p)
+{
+    if ((p->flags & (KVD_PLAN_QUEUE_ORDER | KVD_PLAN_PERSISTENT)) || p->by_descriptor || p->dst_descents == 0) return KVD_ORDER_QUEUE;
+    const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
+    const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
+    if (p->item_bound < 4 * p->desc_estimate) return (always || pieces >= (1u << 17)) ? KVD_ORDER_REGIONS : KVD_ORDER_QUEUE;
+    if (p->item_bound <= kSortItemsPerDesc * p->desc_estimate && p->geo.mode < kRelayoutHT2TH)
+        return (always || pieces >= (1u << 18)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
+    return KVD_ORDER_QUEUE;
+}
+
 // The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
 int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
 {
@@ -428,29 +446,17 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
             KVD_HIP(hipGetLastError());
             return KVD_OK;
         }
-        // descriptors of at most eight work items on average (estimated on the host from the runs in the
-        // block tables): scattered 4-32 KiB pieces, which move faster in the order of their destination.
-        // Below four items per descriptor the items are grouped by region (one launch of about 8 us, which
-        // pays from half a GiB of payload on); from four to eight whole descriptors are sorted (two
-        // launches, 20-55 us: level with the gain of one pull at a GiB, ahead beyond).  Re-layout plans gain
-        // nothing from the sort (measured), and a queue that never steps back in the destination pool is in that
-        // order already.
-        const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
-        const bool group_items = p->item_bound < 4 * p->desc_estimate;
-        const bool sort_descriptors = !group_items && p->item_bound <= kSortItemsPerDesc * p->desc_estimate &&
-                                      p->geo.mode < kRelayoutHT2TH;
-        const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
-        if (!(p->flags & KVD_PLAN_QUEUE_ORDER) && p->dst_descents > 0 &&
-            ((group_items && (always || pieces >= (1u << 17))) || (sort_descriptors && (always || pieces >= (1u << 18))))) {
+        const uint32_t order = work_order(p);
+        if (order != KVD_ORDER_QUEUE) {
             // recorded into a graph, the ordering runs at every replay and the plan still counts
             // as unordered for pulls outside the graph
             const bool capturing = is_capturing(stream);
             if (p->order_stale || capturing) {
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, p->items_dev,
-                                   p->ordered_dev, p->hdr_dev, p->desc_dev, p->desc_hi_dev, p->order_dev, group_items ? 1u : 0u,
-                                   p->order_shift, p->geo.wide);
+                                   p->ordered_dev, p->hdr_dev, p->desc_dev, p->desc_hi_dev, p->order_dev,
+                                   order == KVD_ORDER_REGIONS ? 1u : 0u, p->order_shift, p->geo.wide);
                 KVD_HIP(hipGetLastError());
-                if (!group_items) {
+                if (order == KVD_ORDER_SORTED) {
                     hipLaunchKernelGGL(kvd_order_copy_kernel, dim3((uint32_t)(p->item_bound / 256 + 1)), dim3(256), 0,
                                        (hipStream_t)stream, p->items_dev, p->ordered_dev, p->hdr_dev, p->order_dev);
                     KVD_HIP(hipGetLastError());
@@ -1294,6 +1300,8 @@ int kvd_plan_stats(kvd_plan_t *p, void *stream, kvd_stats_t *out)
         KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
         out->num_descriptors = h.n_desc;
         out->num_work_items = h.n_items;
+        // the device keeps the queue order when merging made the descriptors longer than the host expected
+        out->work_order = (uint64_t)h.n_items > (uint64_t)kSortItemsPerDesc * h.n_desc ? (uint32_t)KVD_ORDER_QUEUE : work_order(p);
     }
     return KVD_OK;
 }

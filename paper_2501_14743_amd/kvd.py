@@ -29,6 +29,7 @@ KVD_PLAN_QUEUE_ORDER = 8
 KVD_PLAN_DESTINATION_ORDER = 64
 KVD_PLAN_WIDE_OFFSETS = 16
 KVD_PLAN_COMPLETE_PER_REQUEST = 32
+KVD_ORDER_QUEUE, KVD_ORDER_REGIONS, KVD_ORDER_SORTED = 0, 1, 2
 LAYOUTS = {"BHTD": KVD_LAYOUT_BHTD, "BTHD": KVD_LAYOUT_BTHD}
 
 
@@ -65,7 +66,8 @@ class kvd_stats_t(ctypes.Structure):
     _fields_ = [("num_requests", ctypes.c_uint32), ("relayout", ctypes.c_uint32),
                 ("num_src_blocks", ctypes.c_uint64), ("num_dst_blocks", ctypes.c_uint64),
                 ("num_transactions", ctypes.c_uint64), ("num_descriptors", ctypes.c_uint64),
-                ("num_work_items", ctypes.c_uint64), ("payload_bytes", ctypes.c_uint64)]
+                ("num_work_items", ctypes.c_uint64), ("payload_bytes", ctypes.c_uint64),
+                ("work_order", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 _lib: Optional[ctypes.CDLL] = None

@@ -619,7 +619,7 @@ def test_region_ordering_of_short_scattered_transactions():
     x.pull()
     x.stream.synchronize()
     stt = x.plan.stats(sh)
-    assert stt["num_work_items"] == n == stt["num_descriptors"]
+    assert stt["num_work_items"] == n == stt["num_descriptors"] and stt["work_order"] == kvd.KVD_ORDER_REGIONS
     want = wl.host_pool_sentinel(g)
     tl.oracle_pull_workload(wl.Workload("big", g, g, [big], "bf16", 0), src_host, want)
     G.assert_bytes_equal(dst.cpu().numpy(), want, "region-ordered pull")
@@ -628,6 +628,7 @@ def test_region_ordering_of_short_scattered_transactions():
     wq = wl.Workload("queue-order", g, g, [big], "bf16", 41)
     y = G.GpuTransfer(wq, src, dst2, flags=kvd.KVD_PLAN_QUEUE_ORDER).run()
     G.assert_bytes_equal(dst2.cpu().numpy(), want, "queue-order pull")
+    assert y.plan.stats(y.stream.cuda_stream)["work_order"] == kvd.KVD_ORDER_QUEUE
     y.close()
     # appending to the plan re-orders on the next pull; a second pull reuses the order
     x.plan.build_descriptors(extra.src_table, extra.dst_table, extra.seq_len, 0, g.num_layers, sh)
@@ -702,9 +703,10 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
     G.assert_bytes_equal(dst.cpu().numpy(), want, case)
     st = x.plan.stats(sh)
     if case == "long-after-all":
-        assert st["num_descriptors"] == 2 and st["num_work_items"] == 1600, st
+        assert st["num_descriptors"] == 2 and st["num_work_items"] == 1600 and st["work_order"] == kvd.KVD_ORDER_QUEUE, st
     else:
-        assert 4 * st["num_descriptors"] <= st["num_work_items"] <= 8 * st["num_descriptors"], st  # the sorted form was taken
+        assert 4 * st["num_descriptors"] <= st["num_work_items"] <= 8 * st["num_descriptors"], st
+        assert st["work_order"] == kvd.KVD_ORDER_SORTED, st
     if case == "batch-per-request":
         dst.view(torch.int16).fill_(wl.SENTINEL16)
         words = torch.zeros(len(reqs), dtype=torch.int64, device="cuda")
