@@ -1311,6 +1311,8 @@ def _random_case(seed):
         foldable = gs.block_major and gd.block_major and (lay_s == lay_d or hk == 1)
         if foldable and not (flags & kvd.KVD_PLAN_PERSISTENT) and rng.random() < 0.5:
             flags |= kvd.KVD_PLAN_WIDE_OFFSETS
+    if not (flags & kvd.KVD_PLAN_PERSISTENT) and rng.random() < 0.5:
+        flags |= kvd.KVD_PLAN_DESTINATION_ORDER  # short descriptors are grouped or sorted however small the transfer
     return gs, gd, reqs, ranges, flags, batch
 
 
@@ -1340,7 +1342,7 @@ def test_random_small_transfers(seed):
     G.assert_bytes_equal(src.cpu().numpy(), src_host, f"random case {seed}: source changed")
     plan.close()
     # the same requests, one call each, through the entry point that allocates nothing
-    carried = flags & (kvd.KVD_PLAN_NO_COALESCE | kvd.KVD_PLAN_WHOLE_BLOCKS)
+    carried = flags & (kvd.KVD_PLAN_NO_COALESCE | kvd.KVD_PLAN_WHOLE_BLOCKS | kvd.KVD_PLAN_DESTINATION_ORDER)
     dst2 = G.device_pool_from_host(wl.host_pool_sentinel(gd))
     sd, dd = kvd.pool_desc(src.data_ptr(), gs), kvd.pool_desc(dst2.data_ptr(), gd)
     torch.cuda.synchronize()
