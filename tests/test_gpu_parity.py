@@ -682,7 +682,7 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
         # straight stretches, everything merges into two descriptors, and the device keeps the queue order after all
         g = wl.PoolGeometry(2, 1024, 64, 1, 128, 2, wl.BTHD)
         gd = wl.PoolGeometry(2, 512, 128, 1, 128, 2, wl.BTHD)
-        reqs = [wl.Request(400 * 64, np.arange(100, 500, dtype=np.int32),
+        reqs = [wl.Request(400 * 64, np.concatenate([np.arange(300, 500), np.arange(100, 300)]).astype(np.int32),
                            np.concatenate([np.arange(150, 250), np.arange(50, 150)]).astype(np.int32))]
     gd = gd if case == "long-after-all" else g
     w = wl.Workload(case, g, gd, reqs, "bf16", 77)
