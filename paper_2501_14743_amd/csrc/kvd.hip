@@ -417,7 +417,7 @@ uint32_t work_order(const kvd_plan *p)
 // The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
 int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
 {
-    PullArgs a;
+    PullArgs a{};
     a.src_base = (const unsigned char *)p->src.base;
     a.dst_base = (unsigned char *)p->dst.base;
     a.items = p->items_dev;
@@ -430,6 +430,7 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
     a.announce = nullptr;
     a.announce_value = 0;
     a.announce_n = 0;
+    a.flat_deal = 0;
     constexpr int T = 64;
     if (p->flags & KVD_PLAN_PERSISTENT) {
         for (const ReqHost &r : p->reqs)
@@ -468,6 +469,10 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
                 if (!capturing) p->order_stale = false;
             }
             a.items = p->ordered_dev;
+            // sorted lone blocks that take an eighth of the destination pool or more: measured 73.3 against 71.2 %
+            // of HBM peak (2048 lone 32 KiB blocks of 16384) and 75.9 against 73.7 % (4096) with the flat deal,
+            // 64.7 against 67.2 % for 512 of them
+            a.flat_deal = (order == KVD_ORDER_SORTED && p->used_dst * 8 >= p->dst.num_blocks) ? 1u : 0u;
         }
         // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
         const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;
@@ -1037,7 +1042,7 @@ int kvd_pull_notify(kvd_plan_t *p, uint64_t *words, uint64_t value, void *stream
         const ReqHost &r = p->reqs[k];
         const int side_i = (int)(turn % kNotifyStreams);
         hipStream_t side = p->notify_stream[side_i];
-        PullArgs a;
+        PullArgs a{};
         a.src_base = (const unsigned char *)p->src.base;
         a.dst_base = (unsigned char *)p->dst.base;
         a.items = p->items_dev;  // queue order: a group's work items are one range of the table
@@ -1219,7 +1224,7 @@ int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_
     KVD_HIP(hipStreamSynchronize(st));
     Header h;
     KVD_HIP(hipMemcpy(&h, p->hdr_dev, sizeof(h), hipMemcpyDeviceToHost));
-    PullArgs a;
+    PullArgs a{};
     a.src_base = (const unsigned char *)p->src.base;
     a.dst_base = (unsigned char *)p->dst.base;
     a.items = p->items_dev;
@@ -1232,6 +1237,7 @@ int kvd_pull_staged(kvd_plan_t *p, void *send_buffer, void *recv_buffer, uint64_
     a.announce = nullptr;
     a.announce_value = 0;
     a.announce_n = 0;
+    a.flat_deal = 0;
     const uint32_t cap = (uint32_t)std::min<uint64_t>(buffer_bytes / 4096, 1u << 20);
     for (uint32_t y = 0; y < a.slabs; ++y)
         for (uint32_t c0 = 0; c0 < h.n_items; c0 += cap) {

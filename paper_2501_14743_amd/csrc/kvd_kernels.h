@@ -546,6 +546,10 @@ struct PullArgs {
     uint64_t *announce;
     uint64_t announce_value;
     uint32_t announce_n;
+    // 1: workgroups are dealt to the XCDs item by item whatever the descriptors look like (lone blocks
+    // sorted by destination that fill an eighth of the pool or more lie close enough to move like one
+    // contiguous range, for which this deal is the faster one)
+    uint32_t flat_deal;
 };
 
 // Streaming 16-byte store: non-temporal at device scope.  Measured on MI355X, this cache policy
@@ -633,7 +637,8 @@ __global__ __launch_bounds__(64) void kvd_stage_kernel(Geo g, PullArgs a, unsign
 // Workgroups are dealt round-robin to the 8 XCDs.  When descriptors are long on average (at least
 // four work items each) every XCD is given one contiguous eighth of the item list, so that one
 // XCD's L2 sees whole runs (+3..5 % of HBM peak measured on 32 KiB-block transfers); with short,
-// scattered descriptors the plain order is kept (the contiguous deal measured 2 % slower there).
+// scattered descriptors the plain order is kept (the contiguous deal measured 2 % slower there),
+// and so it is when the host asks for it (PullArgs::flat_deal).
 // Returns false if there is nothing to do for this workgroup.
 template <int T>
 __device__ __forceinline__ bool pick_piece(const Header h, const PullArgs &a, uint32_t b, uint32_t *piece)
@@ -645,7 +650,7 @@ __device__ __forceinline__ bool pick_piece(const Header h, const PullArgs &a, ui
         if (a.req_end < a.n_req) hi = a.req_item[a.req_end];
     }
     const uint32_t pieces = (hi - lo) * kParts;
-    if (h.n_items >= 4 * h.n_desc) {
+    if (h.n_items >= 4 * h.n_desc && !a.flat_deal) {
         const uint32_t per = (pieces + 7) >> 3;
         if ((b >> 3) >= per) return false;
         b = (b & 7) * per + (b >> 3);
