@@ -392,8 +392,8 @@ def main() -> int:
         extras["no_coalesce_pull_us"] = us
         extras["no_coalesce_descriptors"] = y.plan.stats(sh)["num_descriptors"]
         y.close()
-        # plans of short transactions: the same pull without grouping the work items by destination region
-        if stats["num_work_items"] < 4 * stats["num_transactions"]:
+        # plans whose work items the library puts in destination order: the same pull in queue order
+        if stats["work_order"] != kvd.KVD_ORDER_QUEUE:
             y = G.GpuTransfer(w, src, dst, flags=kvd.KVD_PLAN_QUEUE_ORDER, stream=stream)
             y.build(batch)
             extras["queue_order_pull_us"] = timed(lambda: y.plan.pull(sh), 10)
@@ -790,7 +790,8 @@ def main() -> int:
                    "block_tokens": [w.src.block_tokens, w.dst.block_tokens],
                    "layouts": [w.src.layout, w.dst.layout], "pool_blocks": [w.src.num_blocks, w.dst.num_blocks],
                    "payload_bytes": payload, "descriptors": stats["num_descriptors"],
-                   "transactions": stats["num_transactions"], "work_items": stats["num_work_items"]},
+                   "transactions": stats["num_transactions"], "work_items": stats["num_work_items"],
+                   "work_order": ("queue", "destination regions", "sorted by destination")[stats["work_order"]]},
         "us_per_request_batch": ms_per_step * 1e3,
         "pct_of_peak": 100.0 * achieved / PEAK_HBM_GBPS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
