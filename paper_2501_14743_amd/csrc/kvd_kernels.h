@@ -776,21 +776,37 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
                 s_idx[i] = (uint16_t)i;
             }
             __syncthreads();
-            for (uint32_t k = 2; k <= np2; k <<= 1)
-                for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-                    for (uint32_t t = tid; t < np2 / 2; t += kBuildThreads) {
-                        const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
-                        const uint32_t x = s_key[lo], y = s_key[hi];
-                        if ((x > y) == ((lo & k) == 0)) {
-                            s_key[lo] = y;
-                            s_key[hi] = x;
-                            const uint16_t ix = s_idx[lo];
-                            s_idx[lo] = s_idx[hi];
-                            s_idx[hi] = ix;
-                        }
+            // One compare-exchange stage of the bitonic network: pair t is (lo, lo | j), lo with bit j clear.
+            auto stage = [&](uint32_t k, uint32_t j) {
+                for (uint32_t t = tid; t < np2 / 2; t += kBuildThreads) {
+                    const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                    const uint32_t x = s_key[lo], y = s_key[hi];
+                    if ((x > y) == ((lo & k) == 0)) {
+                        s_key[lo] = y;
+                        s_key[hi] = x;
+                        const uint16_t ix = s_idx[lo];
+                        s_idx[lo] = s_idx[hi];
+                        s_idx[hi] = ix;
                     }
+                }
+            };
+            for (uint32_t k = 2; k <= np2; k <<= 1) {
+                uint32_t j = k >> 1;
+                for (; j >= 2 * kWave; j >>= 1) {
+                    stage(k, j);
                     __syncthreads();
                 }
+                // Pairs at most 64 apart lie inside one 128-element block, and pairs 64 t .. 64 t + 63 - one wave's -
+                // are exactly the pairs of block t: these stages touch nothing another wave touches, so they need
+                // no workgroup barrier, only the wave's own LDS accesses kept in program order.
+                for (; j > 0; j >>= 1) {
+                    stage(k, j);
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                }
+                if (k >= 2 * kWave) __syncthreads();  // the next k starts with pairs that cross waves
+            }
+            __syncthreads();
             // how many items each sorted position brings, then where its items start within the chunk
             uint32_t c[kPer], sum = 0;
 #pragma unroll
