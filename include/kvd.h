@@ -173,7 +173,8 @@ int kvd_pool_create(const kvd_pool_desc_t *desc, kvd_pool_t **out);
  * units) while both pools stay within 64 GiB and 48 bits beyond; with 48-bit offsets a descriptor
  * never continues across a multiple of 32 GiB from either pool's base (its length keeps 32 bits),
  * so a run that crosses one is two descriptors.
- * Errors: KVD_ERR_INVALID (null, zero capacity), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
+ * Errors: KVD_ERR_INVALID (null, zero capacity, unknown flag bits, KVD_PLAN_QUEUE_ORDER together with
+ * KVD_PLAN_DESTINATION_ORDER), KVD_ERR_MISMATCH (num_kv_heads, head_dim or
  * elem_bytes differ; block sizes of which neither divides the other; KVD_PLAN_WIDE_OFFSETS or a
  * pool above 64 GiB with KVD_PLAN_PERSISTENT, KVD_PLAN_WIDE_OFFSETS without block-major pools),
  * KVD_ERR_RANGE (a block axis above 64 GiB in a plan that is not block-major on both sides with
