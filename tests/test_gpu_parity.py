@@ -916,6 +916,35 @@ def test_one_plan_reused_for_a_hundred_random_batches(block_major):
     plan.close()
 
 
+def test_plans_give_back_what_they_allocate():
+    """300 plans created, built, pulled (with per-request completion: side streams and events too) and released:
+    the device's free memory ends where it started."""
+    w = wl.config2(num_layers=2, pool_blocks=512, tokens=1000)
+    src_host = host_src(w)
+    src, dst = G.device_pool_from_host(src_host), G.device_sentinel_pool(w.dst)
+    words = torch.zeros(1, dtype=torch.int64, device="cuda")
+    stream = torch.cuda.Stream()  # one for all plans: torch's own stream pool grows with every new stream up to 32
+
+    def cycle(n):
+        for i in range(n):
+            x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_COMPLETE_PER_REQUEST if i % 2 else kvd.KVD_PLAN_DESTINATION_ORDER,
+                              stream=stream)
+            x.build()
+            if i % 2:
+                x.plan.pull_notify(words.data_ptr(), i + 1, x.stream.cuda_stream)
+            else:
+                x.pull()
+            x.stream.synchronize()
+            x.close()
+        torch.cuda.synchronize()
+    cycle(20)  # whatever the runtime keeps for itself after first use is allocated by now
+    free0 = torch.cuda.mem_get_info()[0]
+    cycle(300)
+    free1 = torch.cuda.mem_get_info()[0]
+    assert free0 - free1 < (8 << 20), (free0, free1)
+    G.assert_bytes_equal(dst.cpu().numpy(), G.oracle_expected(w, src_host), "after 320 plans")
+
+
 def test_blockwise_memcpy_baseline_gives_the_same_bytes():
     w = wl.config2(num_layers=2, pool_blocks=512, tokens=1000)
     src_host = host_src(w)
