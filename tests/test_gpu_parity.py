@@ -916,6 +916,39 @@ def test_one_plan_reused_for_a_hundred_random_batches(block_major):
     plan.close()
 
 
+def test_two_host_threads_with_their_own_plans():
+    """Handles are for one thread at a time, the library is not: two threads, each with its own pools, plan and stream,
+    create, build, pull, check and release side by side (the handle list and the error text are the shared state)."""
+    import threading
+    errors = []
+
+    def worker(seed):
+        try:
+            w = wl.config2(num_layers=2, pool_blocks=512, tokens=777 + 100 * seed)
+            src_host = host_src(w, seed=seed)
+            want = G.oracle_expected(w, src_host)
+            src = G.device_pool_from_host(src_host)
+            stream = torch.cuda.Stream()
+            for i in range(40):
+                dst = G.device_sentinel_pool(w.dst)
+                x = G.GpuTransfer(w, src, dst, kvd.KVD_PLAN_DESTINATION_ORDER if i % 2 else 0, stream=stream)
+                x.run()
+                with pytest.raises(kvd.KvdError) as e:  # this thread's own error text
+                    x.plan.pull_layers(5 + seed, 4, stream.cuda_stream)
+                assert f"[{5 + seed}, 4)" in str(e.value)
+                G.assert_bytes_equal(dst.cpu().numpy(), want, f"thread {seed}, round {i}")
+                x.close()
+        except BaseException as exc:  # noqa: BLE001 - reported by the main thread
+            errors.append((seed, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_plans_give_back_what_they_allocate():
     """300 plans created, built, pulled (with per-request completion: side streams and events too) and released:
     the device's free memory ends where it started."""
