@@ -233,10 +233,11 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * layers and K/V, as ONE kernel launch on `stream` (section 4.2: all reads are posted without
  * blocking; section 4.3: all layers in a single shot).  Every read is cut into work items of at
  * most 4 KiB and each (work item, layer, K/V) is moved by its own small workgroup, 16 bytes per
- * lane.  When the plan's merged transactions are short (at most eight work items each on average,
- * as for lone blocks of 4 to 32 KiB) the first pull after an append is preceded by one small launch
- * that puts the work items in the order of their destination (by 2 MiB region below four items per
- * transaction, whole transactions sorted by address from four to eight); which bytes are moved does
+ * lane.  When the plan's merged transactions are short (at least three quarters of the work in
+ * transactions of at most eight work items, as for lone blocks of 4 to 32 KiB; judged on the host from
+ * the runs in the block tables) the first pull after an append is preceded by one or two small launches
+ * that put the work items in the order of their destination (by 2 MiB region where transactions below
+ * four items prevail, whole transactions sorted by address otherwise); which bytes are moved does
  * not depend on it.  Re-layout plans between two pools whose blocks are the outermost
  * axis are walked block by block (all slabs of a block together) instead of slab by slab.  May be
  * called repeatedly; a plan with no requests is a no-op.

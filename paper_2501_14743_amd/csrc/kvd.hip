@@ -88,6 +88,15 @@ struct ReqHost {
     uint32_t item_bound;                    // work items per slab before merging (upper bound of what it has)
 };
 
+// What the block tables tell the host about how the plan's memory lies, for the decision in which
+// order kvd_pull walks the work items (a hint for launch decisions only: what is done with the work
+// items is decided on the device from the build kernel's own counts).
+struct OrderHint {
+    uint64_t items_below4;  // work items of pieces shorter than four work items (16 KiB)
+    uint64_t items_4to8;    // ... of pieces of four to eight work items
+    uint64_t src_descents, dst_descents;  // how often the queue steps back in either pool (0: it is in that pool's address order)
+};
+
 }  // namespace
 
 // Side streams that the per-request pulls of kvd_pull_notify take turns on.
@@ -128,8 +137,7 @@ struct kvd_plan {
     std::vector<ReqHost> reqs;
     std::vector<uint8_t> dst_used;  // one byte per destination block
     uint64_t used_src, used_dst, txns_total, item_bound, payload_bytes;
-    uint64_t desc_estimate;         // descriptors after merging as far as the host can tell from the tables (runs of blocks)
-    uint64_t src_descents, dst_descents;  // how often the queue steps back in either pool (0: it is in that pool's address order)
+    OrderHint hint;                 // how the plan's memory lies, as far as the host can tell from the tables
     uint32_t max_layers;            // largest layer count of any request in the plan
     // device / pinned scratch (allocated on first use)
     bool allocated;
@@ -239,24 +247,43 @@ void request_sizes(const Geo &g, uint32_t seq_len, uint32_t *n_txn, uint32_t *it
     }
 }
 
-// Pieces of memory a request consists of on both sides at once, as far as the adjacency of consecutive
-// entries in its two block tables tells: the descriptors it merges into (with KVD_PLAN_NO_COALESCE the
-// descriptors stay apart, but what matters for the order of the work is how the memory lies).  A hint
-// for launch decisions only: what is done with the work items is decided on the device from the build
-// kernel's own counts.
-uint64_t estimate_descriptors(const Geo &g, const int32_t *st, const int32_t *dt, uint32_t seq_len, uint32_t n_txn,
-                              uint64_t *src_descents, uint64_t *dst_descents)
+// Adds one request.  A piece is what the request's memory consists of on both sides at once as far as
+// the adjacency of consecutive entries in the two block tables tells: the descriptors it merges into
+// (with KVD_PLAN_NO_COALESCE the descriptors stay apart, but what matters for the order of the work is
+// how the memory lies).
+void add_order_hint(OrderHint *h, const Geo &g, const int32_t *st, const int32_t *dt, uint32_t seq_len, uint32_t n_txn,
+                    uint32_t items)
 {
-    // how often each table steps back: none at all means the queue is in that side's address order already
     const uint32_t src_blocks = ceil_div(seq_len, g.tb_src), dst_blocks = ceil_div(seq_len, g.tb_dst);
-    for (uint32_t i = 1; i < src_blocks; ++i) *src_descents += st[i] < st[i - 1] ? 1u : 0u;
-    for (uint32_t i = 1; i < dst_blocks; ++i) *dst_descents += dt[i] < dt[i - 1] ? 1u : 0u;
-    if (g.mode >= kRelayoutHT2TH || g.tb_src != g.tb_dst) return n_txn;
-    const uint32_t blocks = ceil_div(seq_len, g.tb_src);
-    uint64_t runs = 1;
-    for (uint32_t i = 1; i < blocks; ++i) runs += (st[i] != st[i - 1] + 1 || dt[i] != dt[i - 1] + 1) ? 1u : 0u;
-    if (g.mode == kSpanHeadMajor && seq_len % g.tb_src) runs += g.hk - 1;  // a partial last block: one piece per head
-    return std::min<uint64_t>(runs, n_txn);
+    for (uint32_t i = 1; i < src_blocks; ++i) h->src_descents += st[i] < st[i - 1] ? 1u : 0u;
+    for (uint32_t i = 1; i < dst_blocks; ++i) h->dst_descents += dt[i] < dt[i - 1] ? 1u : 0u;
+    auto piece = [&](uint64_t units) {
+        const uint64_t n = (units + kChunkUnits - 1) / kChunkUnits;
+        if (n < 4) h->items_below4 += n;
+        else if (n <= kSortItemsPerDesc) h->items_4to8 += n;
+    };
+    if (g.mode >= kRelayoutHT2TH || g.tb_src != g.tb_dst) {
+        // pieces of min(block sizes) tokens; which of them merge is not looked at: all alike, of average size
+        const uint64_t per = n_txn ? (items + n_txn - 1) / n_txn : 0;
+        if (per < 4) h->items_below4 += items;
+        else if (per <= kSortItemsPerDesc) h->items_4to8 += items;
+        return;
+    }
+    const uint32_t whole = seq_len / g.tb_src, tail = seq_len % g.tb_src;
+    const uint64_t block_units = (uint64_t)g.tb_src * g.hk * g.du;
+    const bool tail_per_head = g.mode == kSpanHeadMajor;  // a partial last block is then one piece per head
+    const uint32_t in_runs = (tail && !tail_per_head) ? whole + 1 : whole;  // table entries that form runs
+    uint64_t run_units = 0;
+    for (uint32_t i = 0; i < in_runs; ++i) {
+        if (i > 0 && (st[i] != st[i - 1] + 1 || dt[i] != dt[i - 1] + 1)) {
+            piece(run_units);
+            run_units = 0;
+        }
+        run_units += (i < whole) ? block_units : (uint64_t)tail * g.hk * g.du;
+    }
+    if (run_units) piece(run_units);
+    if (tail && tail_per_head)
+        for (uint32_t head = 0; head < g.hk; ++head) piece((uint64_t)tail * g.du);
 }
 
 // Frees whatever of the plan's scratch exists (pointers are null until allocated).
@@ -393,24 +420,28 @@ const kvd_pool *as_pool(const void *h)
     return p->tag == kPoolTag ? p : nullptr;
 }
 
-// How kvd_pull walks the plan's work items, as the host decides it from the block tables.  Descriptors
-// of at most eight work items on average (estimated from the runs in the tables) are scattered 4-32 KiB
-// pieces, which move faster in the order of their destination.  Below four items per descriptor the
+// How kvd_pull walks the plan's work items, as the host decides it from the block tables.  Scattered
+// pieces of 4-32 KiB move faster in the order of their destination; longer ones do not (measured: runs of
+// two 32 KiB blocks gain 1.5 points, about what the sort costs, the 1-8 block runs of the 8192-token
+// configuration lose one, and a dense batch of 1024 short requests - lone blocks and runs mixed, six work
+// items per descriptor on average - loses six).  So the work is reordered only if at least three quarters
+// of it sits in pieces of at most eight work items.  If most of that is in pieces below four items, the
 // items are grouped by region (one launch of about 8 us, which pays from half a GiB of payload on);
-// from four to eight whole descriptors are sorted (two launches, 20-55 us: level with the gain of one
-// pull at a GiB, ahead beyond).  Re-layout plans gain nothing from the sort (measured); a queue that never
-// steps back in the destination pool is in that order already, and one that never steps back in the
-// source pool reads in address order, which the sort would give up for about as much as it gains (measured:
-// 70.4 against 71.5 % of HBM peak for 512 lone destination blocks).
+// otherwise whole descriptors are sorted (two launches, 18-50 us: level with the gain of one pull at a
+// GiB, ahead beyond).  Re-layout plans gain nothing from the sort (measured); a queue that never steps
+// back in the destination pool is in that order already, and one that never steps back in the source pool
+// reads in address order, which the sort would give up for about as much as it gains (measured: 70.4
+// against 71.5 % of HBM peak for 512 lone destination blocks).
 uint32_t work_order(const kvd_plan *p)
 {
     if ((p->flags & (KVD_PLAN_QUEUE_ORDER | KVD_PLAN_PERSISTENT)) || p->by_descriptor) return KVD_ORDER_QUEUE;
-    if (p->dst_descents == 0 || p->src_descents == 0) return KVD_ORDER_QUEUE;
+    const OrderHint &h = p->hint;
+    if (h.dst_descents == 0 || h.src_descents == 0) return KVD_ORDER_QUEUE;
+    if ((h.items_below4 + h.items_4to8) * 4 < p->item_bound * 3) return KVD_ORDER_QUEUE;
     const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
     const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
-    if (p->item_bound < 4 * p->desc_estimate) return (always || pieces >= (1u << 17)) ? KVD_ORDER_REGIONS : KVD_ORDER_QUEUE;
-    if (p->item_bound <= kSortItemsPerDesc * p->desc_estimate && p->geo.mode < kRelayoutHT2TH)
-        return (always || pieces >= (1u << 18)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
+    if (h.items_below4 >= h.items_4to8) return (always || pieces >= (1u << 17)) ? KVD_ORDER_REGIONS : KVD_ORDER_QUEUE;
+    if (p->geo.mode < kRelayoutHT2TH) return (always || pieces >= (1u << 18)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
     return KVD_ORDER_QUEUE;
 }
 
@@ -776,7 +807,8 @@ int kvd_plan_reset(kvd_plan_t *p)
         for (uint32_t i = 0; i < r.n_dst; ++i)
             p->dst_used[(uint32_t)p->tables_dst[r.table_off_dst + i]] = 0;
     p->reqs.clear();
-    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = p->desc_estimate = p->src_descents = p->dst_descents = 0;
+    p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = 0;
+    p->hint = OrderHint{};
     p->max_layers = 0;
     return KVD_OK;
 }
@@ -907,10 +939,10 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         request_sizes(g, seq_len, &n_txn, &items);
         if (!p->reqs.empty()) {
             const ReqHost &prev = p->reqs.back();
-            if (src_tbls[k][0] < p->tables_src[prev.table_off_src + prev.n_src - 1]) ++p->src_descents;
-            if (dst_tbls[k][0] < p->tables_dst[prev.table_off_dst + prev.n_dst - 1]) ++p->dst_descents;
+            if (src_tbls[k][0] < p->tables_src[prev.table_off_src + prev.n_src - 1]) ++p->hint.src_descents;
+            if (dst_tbls[k][0] < p->tables_dst[prev.table_off_dst + prev.n_dst - 1]) ++p->hint.dst_descents;
         }
-        p->desc_estimate += estimate_descriptors(g, src_tbls[k], dst_tbls[k], seq_len, n_txn, &p->src_descents, &p->dst_descents);
+        add_order_hint(&p->hint, g, src_tbls[k], dst_tbls[k], seq_len, n_txn, items);
         p->reqs.push_back(r);
     }
     p->max_layers = std::max(p->max_layers, slab_layers);
@@ -1168,7 +1200,7 @@ int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, con
     // the host's bookkeeping of a plan that holds this one request
     p->txns_total = n_txn;
     p->item_bound = items;
-    p->desc_estimate = estimate_descriptors(g, src_tbl, dst_tbl, len, n_txn, &p->src_descents, &p->dst_descents);
+    add_order_hint(&p->hint, g, src_tbl, dst_tbl, len, n_txn, items);
     p->payload_bytes = ((uint64_t)len * slab_layers * g.hk * g.du * kUnitBytes) << g.kv_shift;
     p->max_layers = slab_layers;
     p->order_stale = true;

@@ -640,7 +640,7 @@ def test_region_ordering_of_short_scattered_transactions():
 
 
 @pytest.mark.parametrize("case", ["lone-16KiB", "lone-16KiB-two-sort-chunks", "mixed-runs", "partial-heads",
-                                  "block-major-wide", "batch-per-request", "no-coalesce", "long-after-all"])
+                                  "block-major-wide", "batch-per-request", "no-coalesce", "long-after-all", "mostly-long"])
 def test_descriptor_sort_of_lone_medium_blocks(case):
     """Descriptors of four to eight work items are sorted by destination address before the pull
     (KVD_PLAN_DESTINATION_ORDER asks for it at any size): the bytes moved and the descriptor list stay the oracle's.
@@ -656,9 +656,9 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
         g = wl.PoolGeometry(1, 9600, 64, 1, 128, 2, wl.BHTD)            # 9000 descriptors: more than are sorted together
         reqs = [wl.Request(9000 * 64, wl.scattered_table(rng, 9600, 9000), wl.scattered_table(rng, 9600, 9000))]
     elif case == "mixed-runs":
-        g = wl.PoolGeometry(2, 4096, 16, 4, 128, 2, wl.BHTD)            # 16 KiB blocks; runs of 1..3
+        g = wl.PoolGeometry(2, 4096, 16, 4, 128, 2, wl.BHTD)            # 16 KiB blocks; runs of 1 and 2 (4 and 8 work items)
         free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
-        reqs = [wl.Request(500 * 16, wl.fragmented_allocation(rng, free_s, 500, 3), wl.fragmented_allocation(rng, free_d, 500, 3))]
+        reqs = [wl.Request(500 * 16, wl.fragmented_allocation(rng, free_s, 500, 2), wl.fragmented_allocation(rng, free_d, 500, 2))]
     elif case == "partial-heads":
         g = wl.PoolGeometry(2, 2048, 64, 4, 64, 2, wl.BHTD)             # 32 KiB blocks, tail of 5 tokens: 4 pieces of 640 B
         reqs = [wl.Request(300 * 64 + 5, wl.scattered_table(rng, 2048, 301), wl.scattered_table(rng, 2048, 301))]
@@ -673,6 +673,11 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
         reqs = []
         for n in (300, 1, 40, 500):
             reqs.append(wl.Request(n * 64 - 1, wl.fragmented_allocation(rng, free_s, n, 1), wl.fragmented_allocation(rng, free_d, n, 1)))
+    elif case == "mostly-long":
+        # lone blocks and runs of up to six: less than three quarters of the work sits in short pieces, the queue order stays
+        g = wl.PoolGeometry(2, 4096, 16, 4, 128, 2, wl.BHTD)
+        free_s, free_d = np.ones(4096, bool), np.ones(4096, bool)
+        reqs = [wl.Request(700 * 16, wl.fragmented_allocation(rng, free_s, 700, 6), wl.fragmented_allocation(rng, free_d, 700, 6))]
     elif case == "no-coalesce":
         g = wl.PoolGeometry(2, 4096, 64, 1, 128, 2, wl.BHTD)            # lone 16 KiB blocks, nothing to merge either way
         flags |= kvd.KVD_PLAN_NO_COALESCE
@@ -704,6 +709,8 @@ def test_descriptor_sort_of_lone_medium_blocks(case):
     st = x.plan.stats(sh)
     if case == "long-after-all":
         assert st["num_descriptors"] == 2 and st["num_work_items"] == 1600 and st["work_order"] == kvd.KVD_ORDER_QUEUE, st
+    elif case == "mostly-long":
+        assert st["work_order"] == kvd.KVD_ORDER_QUEUE, st
     else:
         assert 4 * st["num_descriptors"] <= st["num_work_items"] <= 8 * st["num_descriptors"], st
         assert st["work_order"] == kvd.KVD_ORDER_SORTED, st
