@@ -11,6 +11,7 @@ timed region starts.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import gc
 import json
 import os
@@ -151,6 +152,9 @@ def main() -> int:
                     help="also time the pull of 1024 and 2048 lone blocks of 4 ... 128 KiB per (layer, K/V) (one KV head of "
                          "128 bf16 values, 16 ... 512 tokens per block) in the configuration's pool memory: the "
                          "bandwidth-against-block-size curve of the paper's motivation")
+    ap.add_argument("--order-ab", action="store_true",
+                    help="also time a range of fragmented workloads (lone blocks, short runs, batches of short requests, in "
+                         "the configuration's pool memory) as the library orders their work items and in queue order")
     ap.add_argument("--lone-blocks", action="store_true",
                     help="replace the configuration's block tables by tables in which every block is alone on both sides")
     ap.add_argument("--block-major", action="store_true",
@@ -186,7 +190,7 @@ def main() -> int:
     if args.lone_blocks or args.block_major:
         # variants of a single-request configuration for diagnosis: the same pools and token count with every
         # block alone on both sides, and/or the same memory described as [block][layer][K/V] pools
-        import dataclasses
+
         assert len(w.requests) == 1, "--lone-blocks / --block-major are for the single-request configurations"
         gs, gd, r = w.src, w.dst, w.requests[0]
         name = w.name
@@ -504,7 +508,7 @@ def main() -> int:
         # worst-case fragmentation (every block alone on both sides) of the same token count, in these pools and
         # in the same memory described as block-major pools ([block][layer][K/V]: one range per block over all layers)
         if len(w.requests) == 1 and not w.src.block_major:
-            import dataclasses
+
             tokens = w.requests[0].seq_len
             nblk_s, nblk_d = wl.blocks_for(tokens, w.src.block_tokens), wl.blocks_for(tokens, w.dst.block_tokens)
             for label, geo in (("lone_blocks", (w.src, w.dst)),
@@ -609,7 +613,7 @@ def main() -> int:
                                                      "descriptors": y.plan.stats(sh)["num_descriptors"]}
                     y.close()
             # the same bytes described as block-major pools ([block][layer][K/V]): a lone block is one range over all layers
-            import dataclasses
+
             gbm = dataclasses.replace(w.src, block_major=True)
             for run in (1, 2):
                 rng = np.random.default_rng(w.seed + 2000 + run)
@@ -625,6 +629,69 @@ def main() -> int:
                                                              "descriptors": y.plan.stats(sh)["num_descriptors"]}
                 y.close()
             extras["run_length_sweep"] = sweep
+            x.plan.reset()
+            x.build(batch)
+            x.plan.pull(sh)
+            torch.cuda.synchronize()
+        # the library's choice of the order of the work against the queue order, over a range of fragmented workloads
+        if args.order_ab and not stats["relayout"]:
+            pool_bytes = min(w.src.total_bytes, w.dst.total_bytes)
+            rng = np.random.default_rng(w.seed + 6000)
+            results = {}
+
+            def ab(name, wx, batched=False):
+                row = {}
+                for label, flags in (("default", 0), ("queue_order", kvd.KVD_PLAN_QUEUE_ORDER)):
+                    y = G.GpuTransfer(wx, src, dst, flags, stream=stream)
+                    y.build(batched)
+                    y.plan.pull(sh)
+                    us = min(timed(lambda: y.plan.pull(sh), 10) for _ in range(2))
+
+                    def one_step():
+                        y.plan.reset()
+                        y.build(batched)
+                        y.plan.pull(sh)
+                    one_step()
+                    step_us = min(timed(one_step, 10) for _ in range(2))
+                    st_y = y.plan.stats(sh)
+                    y.close()
+                    row[label] = {"pull_us": us, "step_us": step_us, "pct_of_peak": 2 * st_y["payload_bytes"] / us / 1e3 / PEAK_HBM_GBPS * 100}
+                    if label == "default":
+                        row.update(work_order=st_y["work_order"], descriptors=st_y["num_descriptors"], work_items=st_y["num_work_items"],
+                                   payload_bytes=st_y["payload_bytes"])
+                results[name] = row
+
+            def fragmented(g, tokens, max_run):
+                fs, fd = np.ones(g.num_blocks, bool), np.ones(g.num_blocks, bool)
+                n = wl.blocks_for(tokens, g.block_tokens)
+                return wl.Workload("ab", g, g, [wl.Request(tokens, wl.fragmented_allocation(rng, fs, n, max_run),
+                                                           wl.fragmented_allocation(rng, fd, n, max_run))], "bf16", w.seed)
+            layers = w.src.num_layers
+            g8 = wl.PoolGeometry(layers, min(16384, pool_bytes // (2 * layers * 32768)), 16, 8, 128, 2, wl.BHTD)   # 32 KiB blocks
+            g1 = wl.PoolGeometry(layers, min(8192, pool_bytes // (2 * layers * 4096)), 16, 1, 128, 2, wl.BHTD)     # 4 KiB blocks
+            ga = dataclasses.replace(g8, kv_adjacent=True)                                                         # 64 KiB pieces
+            for tokens in (8192, 32768, 65536):
+                for max_run in (1, 2, 3, 4, 8):
+                    if 4 * wl.blocks_for(tokens, 16) <= g8.num_blocks * 2:
+                        ab(f"32KiB_blocks_{tokens}_tokens_runs_up_to_{max_run}", fragmented(g8, tokens, max_run))
+            for tokens in (16384, 65536):
+                for max_run in (1, 2, 4, 8):
+                    ab(f"4KiB_blocks_{tokens}_tokens_runs_up_to_{max_run}", fragmented(g1, tokens, max_run))
+            ab("kv_adjacent_64KiB_pieces_32768_tokens_lone", fragmented(ga, 32768, 1))
+            ab("32KiB_blocks_32763_tokens_lone_partial_last_block", fragmented(g8, 32763, 1))
+            for n_req, median, hi, max_run in ((256, 256.0, 4096, 1), (256, 256.0, 4096, 2), (1024, 64.0, 1024, 1), (1024, 64.0, 1024, 8),
+                                               (32, 2048.0, 16384, 1), (32, 2048.0, 16384, 8)):
+                lens = wl.lognormal_lengths(rng, n_req, median, 1.0, 16, hi)
+                need = sum(wl.blocks_for(int(t), 16) for t in lens)
+                gb = dataclasses.replace(g8, num_blocks=min(g8.num_blocks, int(need * 1.25) + 1))
+                if need > gb.num_blocks:
+                    continue
+                fs, fd = np.ones(gb.num_blocks, bool), np.ones(gb.num_blocks, bool)
+                reqs = [wl.Request(int(t), wl.fragmented_allocation(rng, fs, wl.blocks_for(int(t), 16), max_run),
+                                   wl.fragmented_allocation(rng, fd, wl.blocks_for(int(t), 16), max_run)) for t in lens]
+                ab(f"batch_of_{n_req}_median_{int(median)}_tokens_runs_up_to_{max_run}_pool_{gb.num_blocks}",
+                   wl.Workload("ab", gb, gb, reqs, "bf16", w.seed), batched=True)
+            extras["order_ab"] = results
             x.plan.reset()
             x.build(batch)
             x.plan.pull(sh)

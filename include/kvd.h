@@ -94,7 +94,7 @@ typedef struct kvd_plan kvd_plan_t;
                                    them in queue order whatever the plan looks like (ablation)      */
 #define KVD_PLAN_DESTINATION_ORDER 64u /* put the work items of short transactions in the order of their
                                    destination (see kvd_pull) whatever the size of the transfer; by default
-                                   that is done only from 0.5 to 1 GiB of payload on, where one pull earns
+                                   that is done only from 0.5 to 1.5 GiB of payload on, where one pull earns
                                    the ordering launches back - a plan that is pulled many times (a recorded
                                    graph) earns them back at any size                                 */
 #define KVD_PLAN_WIDE_OFFSETS 16u /* block-major plans: carry 48-bit offsets even where 32 bits reach the whole

@@ -95,6 +95,7 @@ struct OrderHint {
     uint64_t items_below4;  // work items of pieces shorter than four work items (16 KiB)
     uint64_t items_4to8;    // ... of pieces of four to eight work items
     uint64_t src_descents, dst_descents;  // how often the queue steps back in either pool (0: it is in that pool's address order)
+    bool rough;             // some request's pieces were not walked (block sizes differ): all taken as alike, of average size
 };
 
 }  // namespace
@@ -264,6 +265,7 @@ void add_order_hint(OrderHint *h, const Geo &g, const int32_t *st, const int32_t
     };
     if (g.mode >= kRelayoutHT2TH || g.tb_src != g.tb_dst) {
         // pieces of min(block sizes) tokens; which of them merge is not looked at: all alike, of average size
+        h->rough = true;
         const uint64_t per = n_txn ? (items + n_txn - 1) / n_txn : 0;
         if (per < 4) h->items_below4 += items;
         else if (per <= kSortItemsPerDesc) h->items_4to8 += items;
@@ -428,7 +430,7 @@ const kvd_pool *as_pool(const void *h)
 // of it sits in pieces of at most eight work items.  If most of that is in pieces below four items, the
 // items are grouped by region (one launch of about 8 us, which pays from half a GiB of payload on);
 // otherwise whole descriptors are sorted (two launches, 18-50 us: level with the gain of one pull at a
-// GiB, ahead beyond).  Re-layout plans gain nothing from the sort (measured); a queue that never steps
+// GiB, so from 1.5 GiB on).  Re-layout plans gain nothing from the sort (measured); a queue that never steps
 // back in the destination pool is in that order already, and one that never steps back in the source pool
 // reads in address order, which the sort would give up for about as much as it gains (measured: 70.4
 // against 71.5 % of HBM peak for 512 lone destination blocks).
@@ -441,7 +443,7 @@ uint32_t work_order(const kvd_plan *p)
     const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
     const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
     if (h.items_below4 >= h.items_4to8) return (always || pieces >= (1u << 17)) ? KVD_ORDER_REGIONS : KVD_ORDER_QUEUE;
-    if (p->geo.mode < kRelayoutHT2TH) return (always || pieces >= (1u << 18)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
+    if (p->geo.mode < kRelayoutHT2TH) return (always || pieces >= (3u << 17)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
     return KVD_ORDER_QUEUE;
 }
 
@@ -488,13 +490,14 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
             // as unordered for pulls outside the graph
             const bool capturing = is_capturing(stream);
             if (p->order_stale || capturing) {
+                const uint32_t guard = p->hint.rough ? 1u : 0u;
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, p->items_dev,
                                    p->ordered_dev, p->hdr_dev, p->desc_dev, p->desc_hi_dev, p->order_dev,
-                                   order == KVD_ORDER_REGIONS ? 1u : 0u, p->order_shift, p->geo.wide);
+                                   order == KVD_ORDER_REGIONS ? 1u : 0u, guard, p->order_shift, p->geo.wide);
                 KVD_HIP(hipGetLastError());
                 if (order == KVD_ORDER_SORTED) {
                     hipLaunchKernelGGL(kvd_order_copy_kernel, dim3((uint32_t)(p->item_bound / 256 + 1)), dim3(256), 0,
-                                       (hipStream_t)stream, p->items_dev, p->ordered_dev, p->hdr_dev, p->order_dev);
+                                       (hipStream_t)stream, p->items_dev, p->ordered_dev, p->hdr_dev, p->order_dev, guard);
                     KVD_HIP(hipGetLastError());
                 }
                 if (!capturing) p->order_stale = false;
@@ -503,7 +506,7 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
             // sorted lone blocks that take an eighth of the destination pool or more: measured 73.3 against 71.2 %
             // of HBM peak (2048 lone 32 KiB blocks of 16384) and 75.9 against 73.7 % (4096) with the flat deal,
             // 64.7 against 67.2 % for 512 of them
-            a.flat_deal = (order == KVD_ORDER_SORTED && p->used_dst * 8 >= p->dst.num_blocks) ? 1u : 0u;
+            a.flat_deal = (order == KVD_ORDER_SORTED && !p->hint.rough && p->used_dst * 8 >= p->dst.num_blocks) ? 1u : 0u;
         }
         // sized from the host's pre-merge bound of the item count, rounded up to the 8 XCDs
         const uint64_t gx = (p->item_bound * (kChunkUnits / T) + 7) / 8 * 8;
@@ -1347,7 +1350,8 @@ int kvd_plan_stats(kvd_plan_t *p, void *stream, kvd_stats_t *out)
         out->num_descriptors = h.n_desc;
         out->num_work_items = h.n_items;
         // the device keeps the queue order when merging made the descriptors longer than the host expected
-        out->work_order = (uint64_t)h.n_items > (uint64_t)kSortItemsPerDesc * h.n_desc ? (uint32_t)KVD_ORDER_QUEUE : work_order(p);
+        out->work_order = (p->hint.rough && (uint64_t)h.n_items > (uint64_t)kSortItemsPerDesc * h.n_desc) ? (uint32_t)KVD_ORDER_QUEUE
+                                                                                                           : work_order(p);
     }
     return KVD_OK;
 }

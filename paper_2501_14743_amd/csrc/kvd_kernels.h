@@ -717,7 +717,8 @@ __global__ __launch_bounds__(T) void kvd_pull_by_descriptor_kernel(Geo g, PullAr
 }
 
 // Order of the work items for plans made of short, scattered descriptors; the host chooses the form
-// from the tables, the device keeps the queue order if merging made the descriptors long after all.
+// from the tables; where its picture of them is a rough one (`guard`), the device keeps the queue order
+// if merging made the descriptors long after all.
 //  - group_items (fewer than four work items per descriptor): items are grouped by the region of the
 //    destination slab they write to (buckets of 2^shift units, at least 2 MiB), regions in address
 //    order; a counting sort with the bucket counters in LDS.  Measured on MI355X: 80 layers of 2048
@@ -742,21 +743,23 @@ struct OrderEntry {
     uint32_t to, from;
 };
 
-__device__ __forceinline__ bool sorts_descriptors(const Header h)
+// With `guard` the device has the last word: the host's picture of the descriptors was a rough one
+// (block sizes differ between the pools), and if merging made them long after all the queue order stays.
+__device__ __forceinline__ bool sorts_descriptors(const Header h, uint32_t guard)
 {
-    return h.n_items <= kSortItemsPerDesc * h.n_desc;
+    return !guard || h.n_items <= kSortItemsPerDesc * h.n_desc;
 }
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *items, Item *ordered, const Header *hdr,
                                                                    const Desc *desc, const uint32_t *desc_hi, OrderEntry *order,
-                                                                   uint32_t group_items, uint32_t shift, uint32_t wide)
+                                                                   uint32_t group_items, uint32_t guard, uint32_t shift, uint32_t wide)
 {
     __shared__ uint32_t s_mem[kSortMax + kSortMax / 2];  // bucket counters; or sort keys, then 16-bit indices
     __shared__ uint32_t s_wave[kBuildThreads / kWave];
     uint32_t *const s_count = s_mem;
     const Header h = *hdr;
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    if (!sorts_descriptors(h)) {  // long descriptors: keep the queue order
+    if (!sorts_descriptors(h, guard)) {  // long descriptors: keep the queue order
         for (uint32_t i = tid; i < h.n_items; i += kBuildThreads) ordered[i] = items[i];
         return;
     }
@@ -888,11 +891,11 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
 // position is found by a search over the entries kvd_order_kernel wrote.  grid * 256 >= work items.
 // Does nothing when that kernel kept the queue order (it has then copied the items itself).
 __global__ __launch_bounds__(256) void kvd_order_copy_kernel(const Item *items, Item *ordered, const Header *hdr,
-                                                              const OrderEntry *order)
+                                                              const OrderEntry *order, uint32_t guard)
 {
     const Header h = *hdr;
     const uint32_t o = blockIdx.x * 256 + threadIdx.x;
-    if (!sorts_descriptors(h) || o >= h.n_items) return;
+    if (!sorts_descriptors(h, guard) || o >= h.n_items) return;
     uint32_t lo = 0, hi = h.n_desc;  // largest position whose items start at or before o
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
