@@ -670,21 +670,26 @@ def main() -> int:
             g8 = wl.PoolGeometry(layers, min(16384, pool_bytes // (2 * layers * 32768)), 16, 8, 128, 2, wl.BHTD)   # 32 KiB blocks
             g1 = wl.PoolGeometry(layers, min(8192, pool_bytes // (2 * layers * 4096)), 16, 1, 128, 2, wl.BHTD)     # 4 KiB blocks
             ga = dataclasses.replace(g8, kv_adjacent=True)                                                         # 64 KiB pieces
+            def fits(g, tokens):  # a request takes at most half of the pool, so that runs find room
+                return 2 * wl.blocks_for(tokens, g.block_tokens) <= g.num_blocks
             for tokens in (8192, 32768, 65536):
                 for max_run in (1, 2, 3, 4, 8):
-                    if 4 * wl.blocks_for(tokens, 16) <= g8.num_blocks * 2:
+                    if fits(g8, tokens):
                         ab(f"32KiB_blocks_{tokens}_tokens_runs_up_to_{max_run}", fragmented(g8, tokens, max_run))
             for tokens in (16384, 65536):
                 for max_run in (1, 2, 4, 8):
-                    ab(f"4KiB_blocks_{tokens}_tokens_runs_up_to_{max_run}", fragmented(g1, tokens, max_run))
-            ab("kv_adjacent_64KiB_pieces_32768_tokens_lone", fragmented(ga, 32768, 1))
-            ab("32KiB_blocks_32763_tokens_lone_partial_last_block", fragmented(g8, 32763, 1))
+                    if fits(g1, tokens):
+                        ab(f"4KiB_blocks_{tokens}_tokens_runs_up_to_{max_run}", fragmented(g1, tokens, max_run))
+            if fits(ga, 32768):
+                ab("kv_adjacent_64KiB_pieces_32768_tokens_lone", fragmented(ga, 32768, 1))
+            if fits(g8, 32763):
+                ab("32KiB_blocks_32763_tokens_lone_partial_last_block", fragmented(g8, 32763, 1))
             for n_req, median, hi, max_run in ((256, 256.0, 4096, 1), (256, 256.0, 4096, 2), (1024, 64.0, 1024, 1), (1024, 64.0, 1024, 8),
                                                (32, 2048.0, 16384, 1), (32, 2048.0, 16384, 8)):
                 lens = wl.lognormal_lengths(rng, n_req, median, 1.0, 16, hi)
                 need = sum(wl.blocks_for(int(t), 16) for t in lens)
                 gb = dataclasses.replace(g8, num_blocks=min(g8.num_blocks, int(need * 1.25) + 1))
-                if need > gb.num_blocks:
+                if need * 1.2 > gb.num_blocks:
                     continue
                 fs, fd = np.ones(gb.num_blocks, bool), np.ones(gb.num_blocks, bool)
                 reqs = [wl.Request(int(t), wl.fragmented_allocation(rng, fs, wl.blocks_for(int(t), 16), max_run),
