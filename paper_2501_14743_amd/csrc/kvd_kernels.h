@@ -719,18 +719,19 @@ __global__ __launch_bounds__(T) void kvd_pull_by_descriptor_kernel(Geo g, PullAr
 // Order of the work items for plans made of short, scattered descriptors; the host chooses the form
 // from the tables; where its picture of them is a rough one (`guard`), the device keeps the queue order
 // if merging made the descriptors long after all.
-//  - group_items (fewer than four work items per descriptor): items are grouped by the region of the
+//  - group_items (most of the work in descriptors below four work items): items are grouped by the region of the
 //    destination slab they write to (buckets of 2^shift units, at least 2 MiB), regions in address
 //    order; a counting sort with the bucket counters in LDS.  Measured on MI355X: 80 layers of 2048
 //    lone 4 KiB blocks go from 69 % to 74 % of HBM peak; buckets as coarse as 2 MiB give the whole
 //    gain, the order inside a bucket does not matter.
-//  - otherwise (four to eight work items per descriptor: lone 16 and 32 KiB blocks): whole
+//  - otherwise (most of it in descriptors of four to eight work items: lone 16 and 32 KiB blocks): whole
 //    descriptors are sorted by destination address, kSortMax of them at a time (a bitonic sort of
 //    their keys in LDS), and each keeps its items together and in order.  This kernel writes, per
 //    sorted position, where its items go and where they come from; kvd_order_copy_kernel, a wide
 //    launch right behind it, moves the items.  Measured: 2048 lone 32 KiB blocks out of 16384 go
 //    from 65 % to 72 %, 4096 to 74 %, 512 to 68 %.
-//  - Longer descriptors keep the queue order (sorting runs of two blocks gains 1.5 points, about
+//  - Plans with a quarter or more of the work in longer descriptors keep the queue order and never get
+//    here (sorting runs of two blocks gains 1.5 points, about
 //    what the sort costs; runs of four gain nothing; the 1-8 block runs of the 8192-token
 //    configuration lose a point).
 // One workgroup.
