@@ -237,8 +237,9 @@ int kvd_build_descriptors_batch(kvd_plan_t *plan, uint32_t n_requests,
  * transactions of at most eight work items, as for lone blocks of 4 to 32 KiB; judged on the host from
  * the runs in the block tables) the first pull after an append is preceded by one or two small launches
  * that put the work items in the order of their destination (by 2 MiB region where transactions below
- * four items prevail, whole transactions sorted by address otherwise); which bytes are moved does
- * not depend on it.  Re-layout plans between two pools whose blocks are the outermost
+ * four items prevail, whole transactions sorted by address otherwise; a plan's first request of at
+ * most 1024 transactions is sorted by kvd_build_descriptors itself, without those launches); which
+ * bytes are moved does not depend on it.  Re-layout plans between two pools whose blocks are the outermost
  * axis are walked block by block (all slabs of a block together) instead of slab by slab.  May be
  * called repeatedly; a plan with no requests is a no-op.
  * May be recorded into a HIP graph (it allocates nothing and waits for nothing); the graph then

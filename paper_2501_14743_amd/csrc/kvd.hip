@@ -153,6 +153,7 @@ struct kvd_plan {
     Item *ordered_dev;     // items in the order of their destination (plans of short descriptors)
     OrderEntry *order_dev; // per sorted descriptor: where its items go and come from (kvd_order_kernel -> kvd_order_copy_kernel)
     bool order_stale;      // requests were appended since ordered_dev was last written
+    bool sorted_by_build;  // ordered_dev was written by the plan's only build launch (BuildArgs::sort_inline)
     uint32_t order_shift;  // log2 of the region size in 16-byte units
     Header *hdr_dev;
     // Completion of the build kernels, as far as the host's tables are concerned: every launch
@@ -434,17 +435,31 @@ const kvd_pool *as_pool(const void *h)
 // back in the destination pool is in that order already, and one that never steps back in the source pool
 // reads in address order, which the sort would give up for about as much as it gains (measured: 70.4
 // against 71.5 % of HBM peak for 512 lone destination blocks).
-uint32_t work_order(const kvd_plan *p)
+// `item_bound`: the plan's work items per slab; `by_build`: the sort costs no launches, because the build
+// kernel does it on the way (a fresh plan's only launch, at most kBuildLdsDescs descriptors: about 5 us),
+// and then pays from half a GiB on.
+uint32_t work_order_for(const kvd_plan *p, uint64_t item_bound, bool by_build)
 {
     if ((p->flags & (KVD_PLAN_QUEUE_ORDER | KVD_PLAN_PERSISTENT)) || p->by_descriptor) return KVD_ORDER_QUEUE;
     const OrderHint &h = p->hint;
     if (h.dst_descents == 0 || h.src_descents == 0) return KVD_ORDER_QUEUE;
-    if ((h.items_below4 + h.items_4to8) * 4 < p->item_bound * 3) return KVD_ORDER_QUEUE;
-    const uint64_t pieces = p->item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
+    if ((h.items_below4 + h.items_4to8) * 4 < item_bound * 3) return KVD_ORDER_QUEUE;
+    const uint64_t pieces = item_bound * ((uint64_t)p->max_layers << p->geo.kv_shift);  // 4 KiB each
     const bool always = (p->flags & KVD_PLAN_DESTINATION_ORDER) != 0;
     if (h.items_below4 >= h.items_4to8) return (always || pieces >= (1u << 17)) ? KVD_ORDER_REGIONS : KVD_ORDER_QUEUE;
-    if (p->geo.mode < kRelayoutHT2TH) return (always || pieces >= (3u << 17)) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
+    if (p->geo.mode < kRelayoutHT2TH)
+        return (always || pieces >= (by_build ? (1u << 17) : (3u << 17))) ? KVD_ORDER_SORTED : KVD_ORDER_QUEUE;
     return KVD_ORDER_QUEUE;
+}
+
+uint32_t work_order(const kvd_plan *p) { return work_order_for(p, p->item_bound, p->sorted_by_build); }
+
+// Whether the launch that is about to build `batch_txn` transactions and `batch_items` work items into
+// a plan that holds nothing yet should sort its descriptors by destination itself (BuildArgs::sort_inline).
+bool build_sorts(const kvd_plan *p, bool only_launch_of_a_fresh_plan, uint32_t batch_txn, uint32_t batch_items)
+{
+    return only_launch_of_a_fresh_plan && batch_txn <= kBuildLdsDescs && batch_items <= kInlineItems && !p->geo.wide &&
+           !p->hint.rough && work_order_for(p, batch_items, true) == KVD_ORDER_SORTED;
 }
 
 // The launch(es) of a pull: the whole plan (whole = true), or layers [l0, l1) of the pools.
@@ -489,7 +504,7 @@ int launch_pull(kvd_plan *p, void *stream, bool whole, uint32_t l0, uint32_t l1)
             // recorded into a graph, the ordering runs at every replay and the plan still counts
             // as unordered for pulls outside the graph
             const bool capturing = is_capturing(stream);
-            if (p->order_stale || capturing) {
+            if ((p->order_stale || capturing) && !p->sorted_by_build) {
                 const uint32_t guard = p->hint.rough ? 1u : 0u;
                 hipLaunchKernelGGL(kvd_order_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, p->items_dev,
                                    p->ordered_dev, p->hdr_dev, p->desc_dev, p->desc_hi_dev, p->order_dev,
@@ -560,6 +575,8 @@ BuildArgs build_args(kvd_plan *p, const Geo &g, uint32_t layer_begin, uint32_t n
     a.req_desc = p->req_desc_dev;  // null unless the plan completes request by request
     a.req_item = p->req_item_dev;
     a.req_base = 0;
+    a.sort_inline = 0;
+    a.ordered = p->ordered_dev;
     return a;
 }
 
@@ -813,6 +830,8 @@ int kvd_plan_reset(kvd_plan_t *p)
     p->used_src = p->used_dst = p->txns_total = p->item_bound = p->payload_bytes = 0;
     p->hint = OrderHint{};
     p->max_layers = 0;
+    p->sorted_by_build = false;
+    p->order_stale = true;
     return KVD_OK;
 }
 
@@ -968,6 +987,8 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
         a.fresh = (b0 == 0) ? 1u : 0u;
         a.may_merge_prev = ((b0 > first_new || same_layers) && !(p->flags & KVD_PLAN_COMPLETE_PER_REQUEST)) ? 1u : 0u;
         a.req_base = (uint32_t)b0;
+        p->sorted_by_build = build_sorts(p, b0 == 0 && nb == p->reqs.size(), batch_txn, batch_items);
+        a.sort_inline = p->sorted_by_build ? 1u : 0u;
         p->build_stream = (hipStream_t)stream;
         hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, (hipStream_t)stream, g, a);
         hipError_t launch = hipGetLastError();
@@ -984,7 +1005,7 @@ int kvd_build_descriptors_batch(kvd_plan_t *p, uint32_t n_requests, const int32_
             (void)kvd_plan_reset(p);
             return fail(KVD_ERR_HIP, "launch of the build kernel failed (plan was reset): %s", hipGetErrorString(launch));
         }
-        p->order_stale = true;
+        p->order_stale = !p->sorted_by_build;
         p->txns_total += batch_txn;
         p->item_bound += batch_items;
     }
@@ -1222,6 +1243,9 @@ int kvd_pull_noalloc(const kvd_pool_desc_t *src, const kvd_pool_desc_t *dst, con
     }
     BuildArgs a = build_args(p, g, layer_begin, n_layers, n_txn, items);
     a.first = ReqDev{0, 0, len, 0};
+    p->sorted_by_build = build_sorts(p, true, n_txn, items);
+    a.sort_inline = p->sorted_by_build ? 1u : 0u;
+    p->order_stale = !p->sorted_by_build;
     hipLaunchKernelGGL(kvd_build_kernel, dim3(1), dim3(kBuildThreads), 0, st, g, a);
     KVD_HIP(hipGetLastError());
     if (!a.expand_inline) {

@@ -160,6 +160,11 @@ struct BuildArgs {
     uint32_t *req_desc;        // [requests of the plan] first descriptor
     uint32_t *req_item;        // [requests of the plan] first work item
     uint32_t req_base;         // index of the batch's first request within the plan
+    // 1: a fresh plan's first launch, which adds at most kBuildLdsDescs descriptors and writes its work
+    // items itself, also writes them a second time into `ordered`, the descriptors sorted by destination
+    // address (what kvd_order_kernel and kvd_order_copy_kernel do for larger plans, without their launches)
+    uint32_t sort_inline;
+    Item *ordered;
 };
 
 struct Txn {
@@ -252,6 +257,44 @@ __device__ __forceinline__ uint32_t desc_items(const Geo &g, const Desc &d)
 {
     if (g.mode >= kRelayoutHT2TH) return ((d.a >> 20) * g.hk + g.rows_per_item - 1) / g.rows_per_item;
     return (d.a - d.src16 + kChunkUnits - 1) / kChunkUnits;
+}
+
+// Sorts np2 keys (a power of two, at least one wave's 64) with their 16-bit companions in LDS, ascending:
+// a bitonic network, every lane of the kBuildThreads-lane workgroup takes part, the arrays are final
+// after the call (it ends with a workgroup barrier; one must precede it, after the arrays were filled).
+__device__ __forceinline__ void bitonic_sort_lds(uint32_t *s_key, uint16_t *s_idx, uint32_t np2, uint32_t tid)
+{
+    // One compare-exchange stage: pair t is (lo, lo | j), lo with bit j clear.
+    auto stage = [&](uint32_t k, uint32_t j) {
+        for (uint32_t t = tid; t < np2 / 2; t += kBuildThreads) {
+            const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+            const uint32_t x = s_key[lo], y = s_key[hi];
+            if ((x > y) == ((lo & k) == 0)) {
+                s_key[lo] = y;
+                s_key[hi] = x;
+                const uint16_t ix = s_idx[lo];
+                s_idx[lo] = s_idx[hi];
+                s_idx[hi] = ix;
+            }
+        }
+    };
+    for (uint32_t k = 2; k <= np2; k <<= 1) {
+        uint32_t j = k >> 1;
+        for (; j >= 2 * kWave; j >>= 1) {
+            stage(k, j);
+            __syncthreads();
+        }
+        // Pairs at most 64 apart lie inside one 128-element block, and pairs 64 t .. 64 t + 63 - one wave's -
+        // are exactly the pairs of block t: these stages touch nothing another wave touches, so they need
+        // no workgroup barrier, only the wave's own LDS accesses kept in program order.
+        for (; j > 0; j >>= 1) {
+            stage(k, j);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (k >= 2 * kWave) __syncthreads();  // the next k starts with pairs that cross waves
+    }
+    __syncthreads();
 }
 
 __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildArgs a)
@@ -451,6 +494,59 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_build_kernel(Geo g, BuildAr
                     if (g.wide) dhi = a.desc_hi[from + lo];
                 }
                 a.items[c] = make_item(g, d, dhi, c - d.prefix, a.layers);
+            }
+        }
+    }
+    if (a.sort_inline && a.expand_inline && in_lds && from == 0) {
+        // the same work items once more, in the order of their descriptors' destination addresses
+        uint32_t *const s_key = (uint32_t *)s_end;  // the translation's memory is free by now
+        uint32_t *const s_off = s_key + kBuildLdsDescs;
+        uint16_t *const s_idx = (uint16_t *)(s_off + kBuildLdsDescs);
+        const uint32_t nd = n1;
+        uint32_t np2 = kWave;
+        while (np2 < nd) np2 <<= 1;
+        __syncthreads();
+        if (tid < np2) {
+            s_key[tid] = tid < nd ? s_desc[tid].dst16 : 0xFFFFFFFFu;  // padding sorts to the end
+            s_idx[tid] = (uint16_t)tid;
+        }
+        __syncthreads();
+        bitonic_sort_lds(s_key, s_idx, np2, tid);
+        // items of the descriptor at sorted position tid, then where each position's items start
+        uint32_t cnt = 0;
+        if (tid < nd) {
+            const uint32_t i = s_idx[tid];
+            cnt = ((i + 1 < nd) ? s_desc[i + 1].prefix : n_items) - s_desc[i].prefix;
+        }
+        uint32_t incl = cnt;
+#pragma unroll
+        for (uint32_t o = 1; o < kWave; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        if (lane == kWave - 1) s_wave[wave] = incl;
+        __syncthreads();
+        uint32_t start = incl - cnt;
+        for (uint32_t w = 0; w < wave; ++w) start += s_wave[w];
+        s_off[tid] = start;
+        __syncthreads();
+        const uint32_t per = (n_items + kBuildThreads - 1) / kBuildThreads;
+        const uint32_t o0 = tid * per, o1 = min(n_items, o0 + per);
+        if (o0 < o1) {
+            uint32_t pos = 0, top = nd;  // largest position whose items start at or before o0
+            while (top - pos > 1) {
+                const uint32_t mid = (pos + top) >> 1;
+                if (s_off[mid] <= o0) pos = mid; else top = mid;
+            }
+            Desc d = s_desc[s_idx[pos]];
+            uint32_t next = (pos + 1 < nd) ? s_off[pos + 1] : n_items;
+            for (uint32_t o = o0; o < o1; ++o) {
+                while (o >= next) {
+                    ++pos;
+                    d = s_desc[s_idx[pos]];
+                    next = (pos + 1 < nd) ? s_off[pos + 1] : n_items;
+                }
+                a.ordered[o] = make_item(g, d, 0u, o - s_off[pos], a.layers);
             }
         }
     }
@@ -780,37 +876,7 @@ __global__ __launch_bounds__(kBuildThreads) void kvd_order_kernel(const Item *it
                 s_idx[i] = (uint16_t)i;
             }
             __syncthreads();
-            // One compare-exchange stage of the bitonic network: pair t is (lo, lo | j), lo with bit j clear.
-            auto stage = [&](uint32_t k, uint32_t j) {
-                for (uint32_t t = tid; t < np2 / 2; t += kBuildThreads) {
-                    const uint32_t lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
-                    const uint32_t x = s_key[lo], y = s_key[hi];
-                    if ((x > y) == ((lo & k) == 0)) {
-                        s_key[lo] = y;
-                        s_key[hi] = x;
-                        const uint16_t ix = s_idx[lo];
-                        s_idx[lo] = s_idx[hi];
-                        s_idx[hi] = ix;
-                    }
-                }
-            };
-            for (uint32_t k = 2; k <= np2; k <<= 1) {
-                uint32_t j = k >> 1;
-                for (; j >= 2 * kWave; j >>= 1) {
-                    stage(k, j);
-                    __syncthreads();
-                }
-                // Pairs at most 64 apart lie inside one 128-element block, and pairs 64 t .. 64 t + 63 - one wave's -
-                // are exactly the pairs of block t: these stages touch nothing another wave touches, so they need
-                // no workgroup barrier, only the wave's own LDS accesses kept in program order.
-                for (; j > 0; j >>= 1) {
-                    stage(k, j);
-                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                }
-                if (k >= 2 * kWave) __syncthreads();  // the next k starts with pairs that cross waves
-            }
-            __syncthreads();
+            bitonic_sort_lds(s_key, s_idx, np2, tid);
             // how many items each sorted position brings, then where its items start within the chunk
             uint32_t c[kPer], sum = 0;
 #pragma unroll
